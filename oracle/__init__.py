@@ -1,0 +1,19 @@
+"""CPU oracle for block-sparse attention with repeated query blocks.
+
+TEST INFRASTRUCTURE ONLY.  Plain, slow, fp64 NumPy written from the paper's
+definitions; it shares no code with the HIP library and must never be imported
+by the product package.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` use it.
+
+Pin status (see tests/test_oracle_pins.py): every function below is pinned by
+brute force on tiny inputs, a library routine on a special case, closed forms
+and invariants.  No function is "parity unpinned".
+"""
+from .attention import (  # noqa: F401
+    bf16_bits_to_f64,
+    expand_block_mask,
+    restricted_softmax_rows,
+    sparse_attention,
+    sparse_attention_blocks,
+)
+from .pattern import compile_pattern, pattern_sizes, PatternError  # noqa: F401
