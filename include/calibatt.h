@@ -1,0 +1,142 @@
+/*
+ * calibatt.h - C ABI of the block-sparse attention forward with repeated
+ * query blocks (inference hot path of calibrated sparse attention for video
+ * diffusion transformers), MI355X / gfx950.
+ *
+ * Two stages, as in the paper's Section 3.4 ("Inference stage"):
+ *   1. once per calibrated (timestep, layer) pattern, on the host:
+ *      calibatt_compile_pattern() turns the binary block mask M (Section 3.2:
+ *      entry 1 = block computed, 0 = skipped) and the map of repeated query
+ *      blocks (block-level form of Section 3.3) into read-only index lists;
+ *   2. at every attention call: calibatt_sparse_attn_fwd() runs the tiled
+ *      forward (Section 2, Eq. 3-4: per query block, loop over key/value
+ *      blocks with an online softmax) over the kept blocks only.
+ *
+ * Plain C, no exceptions cross the boundary, no global state is kept between
+ * calls, every buffer is owned by the caller.  All functions return a
+ * calibatt_status (0 = success, negative = error) unless stated otherwise.
+ */
+#ifndef CALIBATT_H
+#define CALIBATT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum calibatt_status {
+  CALIBATT_OK = 0,
+  CALIBATT_ERR_NULL = -1,             /* a required pointer is NULL */
+  CALIBATT_ERR_SHAPE = -2,            /* non-positive or inconsistent dimension */
+  CALIBATT_ERR_UNSUPPORTED = -3,      /* head dim / block size / order not built */
+  CALIBATT_ERR_REPEAT_RANGE = -4,     /* repeat value outside {-1} U [0, nbq) or self */
+  CALIBATT_ERR_REPEAT_CHAIN = -5,     /* source of a repeated block is itself repeated */
+  CALIBATT_ERR_REPEAT_TAIL = -6,      /* short last block used as source of a full block */
+  CALIBATT_ERR_BUFFER_TOO_SMALL = -7, /* col_cap < number of kept blocks */
+  CALIBATT_ERR_PATTERN_MISMATCH = -8, /* pattern was compiled for another H/N/block */
+  CALIBATT_ERR_LAUNCH = -9,           /* the HIP runtime refused the launch */
+  CALIBATT_ERR_NOMEM = -10            /* host scratch allocation failed in compile */
+} calibatt_status;
+
+/* Schedule orders for calibatt_compile_pattern (ids are h*nbq + r). */
+enum {
+  CALIBATT_ORDER_NATURAL = 0,   /* (h, r) ascending */
+  CALIBATT_ORDER_LONGEST = 1,   /* kept count descending, then h, then r */
+  CALIBATT_ORDER_HEAD_LONGEST = 2 /* h ascending, then kept count descending, then r */
+};
+
+/*
+ * Compiled pattern: plain data, all pointers BORROWED (never freed by the
+ * library).  calibatt_compile_pattern() fills it with the HOST buffers the
+ * caller passed in; before calibatt_sparse_attn_fwd() the caller copies the
+ * six arrays to the GPU and stores the DEVICE pointers in a copy of the struct
+ * (the struct itself stays in host memory).
+ *
+ * nbq = ceil(N/block_q), nbk = ceil(N/block_k).  A "row" is one query block of
+ * one head, id = h*nbq + r.
+ */
+typedef struct calibatt_pattern {
+  int32_t H, N, block_q, block_k;
+  int32_t nbq, nbk;
+  int32_t n_work;    /* rows that are computed (not repeated) */
+  int32_t n_repeat;  /* rows that are copies; n_work + n_repeat == H*nbq */
+  int32_t order;     /* schedule order used for `work` */
+  int32_t max_row;   /* largest kept count of any computed row */
+  int64_t nnz;       /* kept blocks over computed rows */
+  const int32_t *row_ptr;    /* [H*nbq + 1] offsets into col_idx; repeated rows are empty */
+  const int32_t *col_idx;    /* [nnz] kept key/value block columns, ascending within a row */
+  const int32_t *repeat_src; /* [H*nbq] -1, or the source query block of the same head */
+  const int32_t *work;       /* [n_work] row ids in schedule order */
+  const int32_t *fan_ptr;    /* [n_work + 1] offsets into fan_dst, per work item */
+  const int32_t *fan_dst;    /* [n_repeat] query blocks that copy work item i, ascending */
+} calibatt_pattern;
+
+/*
+ * Validate a mask / repeat map and count what compile will produce.
+ *
+ * mask   HOST, uint8 [H][nbq][nbk] row-major; any non-zero byte = block kept
+ *        (Section 3.2).  The mask row of a repeated block is ignored.
+ * repeat HOST, int32 [H][nbq]; -1 = computed, s >= 0 = copy of query block s
+ *        of the same head (Section 3.3 at block granularity); NULL = none.
+ * nnz, n_work, n_repeat  HOST outputs, each may be NULL.
+ * Errors: NULL, SHAPE, REPEAT_RANGE / REPEAT_CHAIN / REPEAT_TAIL.
+ */
+int calibatt_pattern_sizes(const uint8_t *mask, const int32_t *repeat, int H, int N, int block_q,
+                           int block_k, int64_t *nnz, int32_t *n_work, int32_t *n_repeat);
+
+/*
+ * Compile a pattern into caller-provided HOST buffers (Section 3.4: the
+ * per-row list of key block-columns to compute, precomputed once; supplement
+ * A.2: padding-free flat layout).  The result is a pure function of the
+ * inputs:
+ *   row_ptr    [H*nbq + 1]  exclusive prefix sum of kept counts in (h, r) order
+ *   col_idx    [col_cap]    first nnz entries written; needs col_cap >= nnz
+ *   repeat_src [H*nbq]
+ *   work       [H*nbq]      first n_work entries written, order per `order`
+ *   fan_ptr    [H*nbq + 1]  first n_work + 1 entries written
+ *   fan_dst    [H*nbq]      first n_repeat entries written
+ * `out` receives the dimensions, counts and the six host pointers.
+ * Errors: as calibatt_pattern_sizes, plus UNSUPPORTED (order),
+ * BUFFER_TOO_SMALL, NOMEM.  On error the output buffers hold garbage.
+ */
+int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repeat, int H, int N, int block_q,
+                             int block_k, int order, int32_t *row_ptr, int32_t *col_idx,
+                             int64_t col_cap, int32_t *repeat_src, int32_t *work, int32_t *fan_ptr,
+                             int32_t *fan_dst, calibatt_pattern *out);
+
+/*
+ * Block-sparse attention forward (Section 2, Eq. 1-4 restricted to kept
+ * blocks; Section 3.4).
+ *
+ * q, k, v  DEVICE, bf16, contiguous [B][H][N][D]; read only.
+ * out      DEVICE, bf16, contiguous [B][H][N][D]; must not alias the inputs.
+ *          Every row < N is written exactly once: a computed row holds
+ *          softmax(scale * q K_kept^T) V_kept with fp32 accumulation, rounded
+ *          to bf16; a row whose block keeps nothing holds zeros; a repeated
+ *          block holds a bitwise copy of the leading rows of its source block.
+ * pattern  HOST struct holding DEVICE pointers (see above).  The same pattern
+ *          serves every batch index (supplement Section A: one mask for the
+ *          conditional and unconditional branch).  Index contents cannot be
+ *          validated on the device: build them with calibatt_compile_pattern.
+ * scale    multiplies the logits before the softmax (1/sqrt(D) in Eq. 1).
+ * stream   hipStream_t (NULL = default stream).  The call only enqueues work.
+ *
+ * Supported: D in {64, 128}, block_q and block_k in {64, 128}.
+ * Errors: NULL, SHAPE, UNSUPPORTED, PATTERN_MISMATCH (pattern compiled for a
+ * different H, N, block_q or block_k), LAUNCH.
+ */
+int calibatt_sparse_attn_fwd(const void *q, const void *k, const void *v, void *out, int B, int H,
+                             int N, int D, int block_q, int block_k,
+                             const calibatt_pattern *pattern, float scale, void *stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *calibatt_strerror(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int calibatt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CALIBATT_H */

@@ -1,0 +1,18 @@
+"""Python binding of libcalibatt (block-sparse attention forward for gfx950).
+
+Argument marshalling only: every step of the path runs in the C/HIP library.
+torch is used for device buffers and streams.  There is no fallback: if the
+library has not been built, loading fails with an error.
+"""
+from .binding import (  # noqa: F401
+    CalibattError,
+    DevicePattern,
+    HostPattern,
+    compile_pattern,
+    library_path,
+    load_library,
+    pattern_sizes,
+    sparse_attn_fwd,
+    strerror,
+    version,
+)

@@ -1,0 +1,213 @@
+"""ctypes marshalling for include/calibatt.h."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG_DIR, "libcalibatt.so")
+_lib = None
+
+
+class CalibattError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class _CPattern(C.Structure):
+    _fields_ = [
+        ("H", C.c_int32), ("N", C.c_int32), ("block_q", C.c_int32), ("block_k", C.c_int32),
+        ("nbq", C.c_int32), ("nbk", C.c_int32),
+        ("n_work", C.c_int32), ("n_repeat", C.c_int32),
+        ("order", C.c_int32), ("max_row", C.c_int32),
+        ("nnz", C.c_int64),
+        ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("repeat_src", C.c_void_p),
+        ("work", C.c_void_p), ("fan_ptr", C.c_void_p), ("fan_dst", C.c_void_p),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libcalibatt.so (built by ``python -m paper_2603_05503_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2603_05503_amd.build` "
+            "(there is no fallback path)"
+        )
+    lib = C.CDLL(_LIB_PATH)
+    i32p, u8p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.POINTER(C.c_int64)
+    lib.calibatt_pattern_sizes.restype = C.c_int
+    lib.calibatt_pattern_sizes.argtypes = [u8p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, i64p, i32p, i32p]
+    lib.calibatt_compile_pattern.restype = C.c_int
+    lib.calibatt_compile_pattern.argtypes = [
+        u8p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+        i32p, i32p, C.c_int64, i32p, i32p, i32p, i32p, C.POINTER(_CPattern),
+    ]
+    lib.calibatt_sparse_attn_fwd.restype = C.c_int
+    lib.calibatt_sparse_attn_fwd.argtypes = [
+        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+        C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+        C.POINTER(_CPattern), C.c_float, C.c_void_p,
+    ]
+    lib.calibatt_strerror.restype = C.c_char_p
+    lib.calibatt_strerror.argtypes = [C.c_int]
+    lib.calibatt_version.restype = C.c_int
+    lib.calibatt_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().calibatt_strerror(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().calibatt_version())
+
+
+def _as_mask(mask, H, nbq, nbk):
+    m = np.ascontiguousarray(mask, dtype=np.uint8)
+    if m.size != H * nbq * nbk:
+        raise ValueError(f"mask has {m.size} entries, expected {H}x{nbq}x{nbk}")
+    return m
+
+
+def _as_repeat(repeat, H, nbq):
+    if repeat is None:
+        return None
+    r = np.ascontiguousarray(repeat, dtype=np.int32)
+    if r.size != H * nbq:
+        raise ValueError(f"repeat has {r.size} entries, expected {H}x{nbq}")
+    return r
+
+
+def _ptr(a, ctype):
+    return None if a is None else a.ctypes.data_as(C.POINTER(ctype))
+
+
+def pattern_sizes(mask, repeat, H, N, block_q, block_k):
+    """(nnz, n_work, n_repeat) via calibatt_pattern_sizes."""
+    lib = load_library()
+    nbq, nbk = -(-N // block_q), -(-N // block_k)
+    m, r = _as_mask(mask, H, nbq, nbk), _as_repeat(repeat, H, nbq)
+    nnz, nw, nr = C.c_int64(0), C.c_int32(0), C.c_int32(0)
+    st = lib.calibatt_pattern_sizes(_ptr(m, C.c_uint8), _ptr(r, C.c_int32), H, N, block_q, block_k,
+                                    C.byref(nnz), C.byref(nw), C.byref(nr))
+    if st != 0:
+        raise CalibattError(st, "calibatt_pattern_sizes")
+    return int(nnz.value), int(nw.value), int(nr.value)
+
+
+@dataclass
+class HostPattern:
+    """Output of calibatt_compile_pattern in host (NumPy) buffers."""
+    H: int
+    N: int
+    block_q: int
+    block_k: int
+    nbq: int
+    nbk: int
+    n_work: int
+    n_repeat: int
+    order: int
+    max_row: int
+    nnz: int
+    row_ptr: np.ndarray
+    col_idx: np.ndarray
+    repeat_src: np.ndarray
+    work: np.ndarray
+    fan_ptr: np.ndarray
+    fan_dst: np.ndarray
+
+    def to_device(self, device="cuda") -> "DevicePattern":
+        return DevicePattern(self, device)
+
+
+def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1) -> HostPattern:
+    lib = load_library()
+    if min(H, N, block_q, block_k) <= 0:
+        raise CalibattError(-2, "calibatt_compile_pattern")
+    nbq, nbk = -(-N // block_q), -(-N // block_k)
+    m, r = _as_mask(mask, H, nbq, nbk), _as_repeat(repeat, H, nbq)
+    nnz, _, _ = pattern_sizes(m, r, H, N, block_q, block_k)
+    rows = H * nbq
+    row_ptr = np.empty(rows + 1, np.int32)
+    col_idx = np.empty(max(nnz, 1), np.int32)
+    repeat_src = np.empty(rows, np.int32)
+    work = np.empty(rows, np.int32)
+    fan_ptr = np.empty(rows + 1, np.int32)
+    fan_dst = np.empty(rows, np.int32)
+    cp = _CPattern()
+    st = lib.calibatt_compile_pattern(
+        _ptr(m, C.c_uint8), _ptr(r, C.c_int32), H, N, block_q, block_k, order,
+        _ptr(row_ptr, C.c_int32), _ptr(col_idx, C.c_int32), nnz, _ptr(repeat_src, C.c_int32),
+        _ptr(work, C.c_int32), _ptr(fan_ptr, C.c_int32), _ptr(fan_dst, C.c_int32), C.byref(cp))
+    if st != 0:
+        raise CalibattError(st, "calibatt_compile_pattern")
+    return HostPattern(
+        H=cp.H, N=cp.N, block_q=cp.block_q, block_k=cp.block_k, nbq=cp.nbq, nbk=cp.nbk,
+        n_work=cp.n_work, n_repeat=cp.n_repeat, order=cp.order, max_row=cp.max_row, nnz=cp.nnz,
+        row_ptr=row_ptr, col_idx=col_idx[:nnz], repeat_src=repeat_src,
+        work=work[: cp.n_work], fan_ptr=fan_ptr[: cp.n_work + 1], fan_dst=fan_dst[: cp.n_repeat],
+    )
+
+
+class DevicePattern:
+    """The six index arrays as int32 torch tensors on the GPU plus the C struct
+    that points at them."""
+
+    _NAMES = ("row_ptr", "col_idx", "repeat_src", "work", "fan_ptr", "fan_dst")
+
+    def __init__(self, hp: HostPattern, device="cuda"):
+        import torch
+
+        self.host = hp
+        self.tensors = {}
+        for name in self._NAMES:
+            a = getattr(hp, name)
+            t = torch.from_numpy(np.ascontiguousarray(a if a.size else np.zeros(1, np.int32)))
+            self.tensors[name] = t.to(device)
+        c = _CPattern()
+        for f in ("H", "N", "block_q", "block_k", "nbq", "nbk", "n_work", "n_repeat", "order", "max_row", "nnz"):
+            setattr(c, f, getattr(hp, f))
+        for name in self._NAMES:
+            setattr(c, name, self.tensors[name].data_ptr())
+        self.c = c
+
+    @property
+    def nnz(self) -> int:
+        return self.host.nnz
+
+
+def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
+                    block_q: Optional[int] = None, block_k: Optional[int] = None, stream=None):
+    """calibatt_sparse_attn_fwd on torch bf16 CUDA tensors [B, H, N, D]."""
+    import torch
+
+    lib = load_library()
+    for t in (q, k, v, out):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
+            raise ValueError("q, k, v, out must be contiguous bf16 CUDA tensors [B, H, N, D]")
+        if t.shape != q.shape:
+            raise ValueError("q, k, v, out must have the same shape")
+    B, H, N, D = q.shape
+    bq = pattern.host.block_q if block_q is None else block_q
+    bk = pattern.host.block_k if block_k is None else block_k
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = lib.calibatt_sparse_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                      B, H, N, D, bq, bk, C.byref(pattern.c), float(scale), C.c_void_p(stream))
+    if st != 0:
+        raise CalibattError(st, "calibatt_sparse_attn_fwd")
+    return out
