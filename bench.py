@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-sparse attention forward on one MI355X.
+
+A "step" is one attention call of the hot path at the Wan-2.1-14B 480p shape
+(B=1, H=40, N=32760, D=128, 128x128 blocks, ~30 % kept blocks, 10 % repeated
+query blocks): select the pre-compiled pattern, launch the kernel over all
+heads, wait for it.  Patterns are compiled once before the timed region (the
+paper builds its skip lists offline, Section 3.4); q/k/v/out are resident in
+HBM.  The metric is computed-block bf16 TFLOP/s = kept blocks * 4*bq*bk*D / t.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6  # 256 CUs x 4096 FLOP/clk/CU x 2.4 GHz (published 2.5 PFLOP/s dense bf16)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="wan480", choices=["tiny", "wan480", "wan720", "mochi"])
+    ap.add_argument("--density", type=float, default=None)
+    ap.add_argument("--repeat-frac", type=float, default=None)
+    ap.add_argument("--order", type=int, default=1)
+    ap.add_argument("--heads", type=int, default=None)
+    ap.add_argument("--no-dense", action="store_true", help="skip the all-ones reference run")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-blocks", type=int, default=48, help="query blocks in the CPU oracle sample")
+    return ap.parse_args()
+
+
+def time_launches(pkg, torch, q, k, v, out, dp, scale, steps, warmup):
+    """Returns (ms_per_step by wall clock, mean kernel ms by HIP events)."""
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        pkg.sparse_attn_fwd(q, k, v, out, dp, scale)
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record(stream)
+        pkg.sparse_attn_fwd(q, k, v, out, dp, scale)
+        stops[i].record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
+    return wall_ms, sum(ev) / len(ev), ev[len(ev) // 2]
+
+
+def cpu_oracle_baseline(wl, n_blocks):
+    """Time the fp64 oracle, as it stands, on a seeded sample of query blocks
+    stratified by kept count; returns the cpu_baseline object."""
+    import numpy as np
+
+    from oracle import sparse_attention_blocks
+
+    try:
+        from threadpoolctl import threadpool_info
+
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    rng = np.random.default_rng(7)
+    heads = rng.choice(wl.H, size=min(4, wl.H), replace=False)
+    per_head = max(1, n_blocks // len(heads))
+    items = []
+    kept = 0
+    for h in sorted(int(x) for x in heads):
+        live = np.flatnonzero(wl.repeat[h] < 0)
+        counts = wl.mask[h, live].astype(bool).sum(axis=1)
+        order = live[np.argsort(counts, kind="stable")]
+        pick = order[np.linspace(0, order.size - 1, per_head).astype(int)]
+        for r in pick:
+            items.append((0, h, int(r)))
+            kept += int(wl.mask[h, r].astype(bool).sum())
+    t0 = time.perf_counter()
+    sparse_attention_blocks(wl.q, wl.k, wl.v, wl.mask, wl.repeat, wl.scale, wl.block_q, wl.block_k, items)
+    dt = time.perf_counter() - t0
+    flops = kept * 4.0 * wl.block_q * wl.block_k * wl.D
+    return {
+        "value": flops / dt / 1e12,
+        "unit": "TFLOP/s",
+        "cores": int(threads),
+        "kind": "oracle",
+        "sample": f"{len(items)} query blocks of {len(heads)} heads stratified by kept count "
+                  f"({kept} kept blocks, {dt:.1f} s, fp64 NumPy, full-width masked softmax)",
+        "seconds": dt,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (heads would shard across GPUs "
+              "without any exchange, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2603_05503_amd as pkg
+    from tests.parity_utils import to_dev
+    from workloads import make_workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    pkg.load_library()
+    torch.cuda.set_device(0)
+
+    wl = make_workload(args.workload, density=args.density, repeat_frac=args.repeat_frac, heads=args.heads)
+    t0 = time.perf_counter()
+    hp = pkg.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, args.order)
+    compile_ms = (time.perf_counter() - t0) * 1e3
+    dp = hp.to_device()
+    q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
+    out = torch.empty_like(q)
+    tile_flops = 4.0 * wl.block_q * wl.block_k * wl.D
+    flops = hp.nnz * wl.B * tile_flops
+
+    wall_ms, ev_mean_ms, ev_med_ms = time_launches(pkg, torch, q, k, v, out, dp, wl.scale, args.steps, args.warmup)
+    value = flops / (wall_ms * 1e-3) / 1e12
+    achieved = flops / (ev_mean_ms * 1e-3) / 1e12
+
+    dense = None
+    if not args.no_dense:
+        wd = make_workload(args.workload, dense=True, with_qkv=False, heads=args.heads)
+        hd = pkg.compile_pattern(wd.mask, wd.repeat, wd.H, wd.N, wd.block_q, wd.block_k, args.order).to_device()
+        d_wall, d_ev, d_med = time_launches(pkg, torch, q, k, v, out, hd, wl.scale, max(3, args.steps // 4), 1)
+        dense = {"ms": d_ev, "tflops": hd.nnz * wl.B * tile_flops / (d_ev * 1e-3) / 1e12,
+                 "speedup_sparse_vs_dense": d_ev / ev_mean_ms}
+
+    result = {
+        "metric": "computed-block bf16 TFLOP/s (% MFMA peak); speedup vs dense @ Wan 480p shape",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{args.workload}: B={wl.B} H={wl.H} N={wl.N} D={wl.D} blocks {wl.block_q}x{wl.block_k}, "
+                        f"mask density {wl.stats.get('density', 0):.3f}, repeated query blocks {wl.stats.get('repeat_frac', 0):.3f}",
+            "kept_blocks": int(hp.nnz),
+            "computed_rows": int(hp.n_work),
+            "repeated_rows": int(hp.n_repeat),
+            "schedule_order": args.order,
+            "pattern_compile_ms": compile_ms,
+        },
+        "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "kernel_ms_mean": ev_mean_ms,
+        "kernel_ms_median": ev_med_ms,
+        "dense_reference": dense,
+        "roofline": {
+            "bound": "mfma",
+            "achieved": achieved,
+            "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": achieved / PEAK_BF16_TFLOPS,
+            "traffic": None,
+        },
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_oracle_baseline(wl, args.cpu_blocks)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
