@@ -44,28 +44,28 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 #define LDS_PTR(T) __attribute__((address_space(3))) T *
 
-struct FwdParams {
-  const uint16_t *q, *k, *v;
-  uint16_t *out;
-  const int32_t *row_ptr, *col_idx, *work, *fan_ptr, *fan_dst;
+struct FwdDims {
   int B, H, N, nbq, nbk, n_work;
   float scale_log2e;
 };
 
 template <int N_OUTSTANDING>
 __device__ __forceinline__ void wait_vmem() {
-  // waits until at most N_OUTSTANDING vector-memory loads of this wave are in flight
-  if constexpr (N_OUTSTANDING == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  else if constexpr (N_OUTSTANDING == 1) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
-  else if constexpr (N_OUTSTANDING == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-  else if constexpr (N_OUTSTANDING == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  else if constexpr (N_OUTSTANDING == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else if constexpr (N_OUTSTANDING == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // waits until at most N_OUTSTANDING vector-memory operations of this wave are in flight
+  static_assert(N_OUTSTANDING == 0 || N_OUTSTANDING == 2 || N_OUTSTANDING == 4 || N_OUTSTANDING == 8 ||
+                N_OUTSTANDING == 16, "add the immediate below");
+  if constexpr (N_OUTSTANDING == 0) asm volatile("s_waitcnt vmcnt(0)");
+  else if constexpr (N_OUTSTANDING == 2) asm volatile("s_waitcnt vmcnt(2)");
+  else if constexpr (N_OUTSTANDING == 4) asm volatile("s_waitcnt vmcnt(4)");
+  else if constexpr (N_OUTSTANDING == 8) asm volatile("s_waitcnt vmcnt(8)");
+  else asm volatile("s_waitcnt vmcnt(16)");
 }
 
-// 16-byte-chunk swizzles.  CH = chunks per row (D/8).  A 256-byte LDS line
-// (all 64 banks) holds 16/CH rows.
+// 16-byte-chunk XOR swizzles of the LDS tiles.  CH = chunks per row (D/8); one
+// 256-byte LDS line (all 64 banks) holds 16/CH rows.
+//  K: 16 lanes reading 16 consecutive rows at one chunk column hit 16 distinct chunks.
+//  V: a transposing read touches 4 consecutive rows x 4 consecutive chunks; they
+//     land on 16 distinct chunks.
 template <int D>
 __device__ __forceinline__ int k_swz(int row) {
   constexpr int CH = D / 8;
@@ -77,30 +77,66 @@ __device__ __forceinline__ int v_swz(int row) {
   return 4 * ((row / (16 / CH)) % (CH / 4));
 }
 
-// Stream one ROWS x D bf16 tile global -> LDS.  Rows >= N are clamped to N-1
-// (their logits are masked later).  LDS chunk (row, c') receives global chunk
-// (row, c' ^ swz(row)).
-template <int D, int ROWS, int NT, bool FOR_V>
-__device__ __forceinline__ void load_tile(const uint16_t *__restrict__ head_base, int row0, int N,
-                                          char *lds_tile, int tid) {
-  constexpr int CH = D / 8;
-  constexpr int CHUNKS = ROWS * CH;
-  constexpr int ITERS = CHUNKS / NT;
-  static_assert(CHUNKS % NT == 0, "tile must split evenly over the workgroup");
-  const int wave_base = (tid / 64) * 64;
-#pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int L = it * NT + tid;
-    const int row = L / CH;
-    const int cs = L % CH;
-    const int c = cs ^ (FOR_V ? v_swz<D>(row) : k_swz<D>(row));
-    int grow = row0 + row;
-    grow = grow < N ? grow : N - 1;
-    const uint16_t *src = head_base + (size_t)grow * D + c * 8;
-    char *dst = lds_tile + (size_t)(it * NT + wave_base) * 16;  // wave-uniform; lane*16 is implicit
-    __builtin_amdgcn_global_load_lds(src, (LDS_PTR(void))dst, 16, 0, 0);
-  }
+// Raw buffer descriptor (V#) over one head's [N][D] bf16 matrix: loads past the
+// end return zero instead of faulting, which is how ragged tails are handled.
+__device__ __forceinline__ u32x4 head_rsrc(const uint16_t *base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  u32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  r[1] = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);  // stride 0, no swizzle
+  r[2] = bytes;
+  r[3] = 0x00020000u;
+  return r;
 }
+
+// One direct-to-LDS load: every lane fetches 16 bytes at rsrc.base + voff + soff
+// and the wave's 1 KB lands at LDS byte address lds_off + 16 * lane.  Issued as
+// inline asm so that the compiler keeps no record of LDS being written by an
+// in-flight vector-memory operation (it would otherwise drain vmcnt before
+// every LDS read); completion is tracked by hand with wait_vmem<>().
+__device__ __forceinline__ void dma_16B_per_lane(const u32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_off) {
+#ifdef CALIBATT_DEBUG_BUILTIN_DMA
+  __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)rsrc[1] << 32) | rsrc[0]), 0, rsrc[2], 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rr, (LDS_PTR(void))(uintptr_t)lds_off, 16, voff, soff, 0, 0);
+  return;
+#endif
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"  // one wait state between the M0 write and the LDS-DMA that reads it
+      "buffer_load_dwordx4 %1, %2, %3 offen lds"
+      :
+      : "s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff)
+      : "m0");
+}
+
+// Stream one ROWS x D bf16 tile global -> LDS.  Each instruction fills 1 KB of
+// LDS; LDS chunk (row, c') receives global chunk (row, c' ^ swz(row)).
+template <int D, int ROWS, int NT, bool FOR_V>
+struct TileLoader {
+  static constexpr int CH = D / 8;
+  static constexpr int RPI = NT / CH;            // rows filled per instruction slab
+  static constexpr int ITERS = ROWS / RPI;
+  static constexpr bool INVARIANT = (RPI % 16) == 0;  // swizzle repeats every 16 rows
+  static_assert(ROWS % RPI == 0, "tile must split evenly over the workgroup");
+
+  static __device__ __forceinline__ uint32_t lane_offset(int tid, int it) {
+    const int row = it * RPI + tid / CH;
+    const int cs = tid % CH;
+    const int c = cs ^ (FOR_V ? v_swz<D>(row) : k_swz<D>(row));
+    return (tid / CH) * (D * 2) + c * 16;
+  }
+
+  // lds_wave_off: LDS byte address of the tile + 1024 * wave index (wave-uniform)
+  static __device__ __forceinline__ void issue(const u32x4 rsrc, int row0, uint32_t lds_wave_off, int tid,
+                                               uint32_t lane_off0) {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const uint32_t voff = INVARIANT ? lane_off0 : lane_offset(tid, it);
+      const uint32_t soff = (uint32_t)(row0 + it * RPI) * (D * 2);
+      dma_16B_per_lane(rsrc, voff, soff, lds_wave_off + it * NT * 16);
+    }
+  }
+};
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   bf16x2 t;
@@ -109,8 +145,32 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
+// After the swap, a holds {x[0..31], x[0..31]} and b holds {x[32..63], x[32..63]}:
+// every lane sees its own value and the one of lane ^ 32.  (Inline asm: the
+// two-result builtin folds both results into one when fed the same operand
+// twice.)  The leading s_nop covers the VALU-write -> permlane-read hazard.
+__device__ __forceinline__ void halves_of(float x, float &a, float &b) {
+  a = x;
+  b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float max_with_other_half(float x) {
+  float a, b;
+  halves_of(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+  float a, b;
+  halves_of(x, a, b);
+  return a + b;
+}
+
 template <int D, int BQ, int BK>
-__global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_kernel(const FwdParams p) {
+__global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_kernel(
+    const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
+    uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
+    const FwdDims p) {
   constexpr int NW = BQ / 32;     // wavefronts per workgroup
   constexpr int NT = NW * 64;     // threads
   constexpr int CH = D / 8;       // 16-byte chunks per row
@@ -119,9 +179,11 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   constexpr int DB = D / 32;      // 32-wide d blocks of O^T
   constexpr int ROWB = D * 2;     // bytes per LDS row
   constexpr int TILE_BYTES = BK * ROWB;
-  constexpr int LOADS_PER_WAVE = (BK * CH) / NT;  // direct-to-LDS instructions per wave and tile
   constexpr int OST = ROWB + 16;  // padded row stride of the output staging tile
   constexpr int LDS_BYTES = (2 * TILE_BYTES > BQ * OST) ? 2 * TILE_BYTES : BQ * OST;
+  using LoadK = TileLoader<D, BK, NT, false>;
+  using LoadV = TileLoader<D, BK, NT, true>;
+  constexpr int LOADS_PER_WAVE = LoadK::ITERS;  // direct-to-LDS instructions per wave and tile
 
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
   char *const ldsK = lds;
@@ -135,31 +197,46 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
 
   const int item = blockIdx.x / p.B;
   const int b = blockIdx.x - item * p.B;
-  const int id = p.work[item];
+  const int id = work[item];
   const int h = id / p.nbq;
   const int r = id - h * p.nbq;
   const int N = p.N;
   const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
-  const uint16_t *__restrict__ Kh = p.k + head_off;
-  const uint16_t *__restrict__ Vh = p.v + head_off;
+  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
+  const u32x4 Vres = head_rsrc(gv + head_off, (uint32_t)N * ROWB);
+  const uint32_t k_lane_off = LoadK::lane_offset(tid, 0);
+  const uint32_t v_lane_off = LoadV::lane_offset(tid, 0);
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
+  const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t ldsK_wave = lds_base + wave_u * 1024;
+  const uint32_t ldsV_wave = ldsK_wave + TILE_BYTES;
 
-  const int cbeg = p.row_ptr[id];
-  const int cend = p.row_ptr[id + 1];
+  const int cbeg = row_ptr[id];
+  const int cend = row_ptr[id + 1];
 
+  // The row's kv-block list is held 64 entries at a time in one VGPR (lane j =
+  // entry j) and read back with v_readlane: no memory operation per tile.
+  const int n_tiles = cend - cbeg;
+  int col_cache = n_tiles > 0 ? col_idx[cbeg + min(lane, n_tiles - 1)] : 0;
+  // first K and V tiles
+  int c_next = 0;
+  if (n_tiles > 0) {
+    c_next = __builtin_amdgcn_readlane(col_cache, 0);
+    LoadK::issue(Kres, c_next * BK, ldsK_wave, tid, k_lane_off);
+    LoadV::issue(Vres, c_next * BK, ldsV_wave, tid, v_lane_off);
+  }
   // Q^T as MFMA B operand: lane (query l32, half g) holds d = 16 s + 8 g + [0,8)
   bf16x8 qreg[DS];
   {
     int qrow = r * BQ + wave * 32 + l32;
     qrow = qrow < N ? qrow : N - 1;
-    const uint16_t *qp = p.q + head_off + (size_t)qrow * D + 8 * g;
+    const uint16_t *qp = gq + head_off + (size_t)qrow * D + 8 * g;
 #pragma unroll
     for (int s = 0; s < DS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
-  }
-  // first K and V tiles (issued after the Q loads: vmem loads retire in order)
-  if (cbeg < cend) {
-    const int c0 = p.col_idx[cbeg];
-    load_tile<D, BK, NT, false>(Kh, c0 * BK, N, ldsK, tid);
-    load_tile<D, BK, NT, true>(Vh, c0 * BK, N, ldsV, tid);
+    // touch the registers here so that the compiler's wait for these loads sits
+    // in front of the loop and not inside it
+#pragma unroll
+    for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qreg[s]));
   }
 
   f32x16 o[DB];
@@ -171,22 +248,32 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   float l_run = 0.f;        // this lane's share of the running row sum
 
   // K operand row for MFMA row i = l32: swap bits 2 and 3 so that the 8 S^T
-  // values a lane holds per 16-key slab belong to 8 consecutive keys.
+  // values a lane holds per 16-key slab belong to 8 consecutive keys.  With the
+  // XOR swizzle the address of k-slab s is k_addr0 ^ (s << 5).
   const int krow_in_kb = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
-  // transposing V read: 16-lane block -> (d sub-block, key half); lane L in block
+  const uint32_t k_addr0 = krow_in_kb * ROWB + ((g ^ k_swz<D>(krow_in_kb)) << 4);
+  // transposing V read: 16-lane block -> (d sub-block, key half); lane L16 in block
   const int L16 = lane & 15;
   const int blk = lane >> 4;
-  const int v_row_off = 8 * (blk >> 1) + (L16 >> 2);                 // + 32 kb + 16 s2 + 4 t
-  const int v_chunk_off = 2 * (blk & 1) + ((L16 & 3) >> 1);          // + 4 db
-  const int v_byte_off = (L16 & 1) * 8;
+  const int v_row_off = 8 * (blk >> 1) + (L16 >> 2);  // + 32 kb + 16 s2 + 4 t
+  uint32_t v_addr[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    v_addr[db] = v_row_off * ROWB + (((4 * db + 2 * (blk & 1) + ((L16 & 3) >> 1)) ^ v_swz<D>(v_row_off)) << 4) +
+                 (L16 & 1) * 8;
 
-  for (int ci = cbeg; ci < cend; ++ci) {
-    const int c = p.col_idx[ci];
-    const bool has_next = ci + 1 < cend;
-    const int c_next = has_next ? p.col_idx[ci + 1] : 0;
+  const float sc = p.scale_log2e;
+
+  for (int ti = 0; ti < n_tiles; ++ti) {
+    const int c = c_next;
+    const bool has_next = ti + 1 < n_tiles;
+    if (has_next) {
+      if (((ti + 1) & 63) == 0) col_cache = col_idx[cbeg + min(ti + 1 + lane, n_tiles - 1)];
+      c_next = __builtin_amdgcn_readlane(col_cache, (ti + 1) & 63);
+    }
 
     // ---- S^T = K Q^T --------------------------------------------------------
-    // K[ci] was issued before V[ci]: allow V's loads to stay in flight.
+    // K[ci] was issued before V[ci]: V's loads may stay in flight.
     wait_vmem<LOADS_PER_WAVE>();
     __syncthreads();
     f32x16 s_acc[KB];
@@ -194,62 +281,62 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.f;
-      const int krow = 32 * kb + krow_in_kb;
-      const char *kbase = ldsK + krow * ROWB;
-      const int sw = k_swz<D>(krow);
 #pragma unroll
       for (int s = 0; s < DS; ++s) {
-        const int cs = (2 * s + g) ^ sw;
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kbase + cs * 16);
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ldsK + ((k_addr0 ^ (s << 5)) + kb * 32 * ROWB));
         s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], s_acc[kb], 0, 0, 0);
       }
     }
     __syncthreads();  // every wave is done with the K tile
-    if (has_next) load_tile<D, BK, NT, false>(Kh, c_next * BK, N, ldsK, tid);
+    if (has_next) LoadK::issue(Kres, c_next * BK, ldsK_wave, tid, k_lane_off);
 
-    // ---- online softmax -----------------------------------------------------
-    const float sc = p.scale_log2e;
-    float m_loc = -INFINITY;
-    if (c == p.nbk - 1 && (N % BK) != 0) {
+    // ---- online softmax (log2 domain) ----------------------------------------
+    if (c == p.nbk - 1 && (N % BK) != 0) {  // keys >= N of the ragged last block
       const int key0 = c * BK + 8 * g;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
-          const float t = s_acc[kb][v] * sc;
-          s_acc[kb][v] = key < N ? t : -INFINITY;
+          if (key >= N) s_acc[kb][v] = sc >= 0.f ? -INFINITY : INFINITY;
         }
-    } else {
+    }
+    float m_loc;
+    if (sc >= 0.f) {
+      m_loc = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s_acc[kb][v] *= sc;
+        for (int v = 0; v < 16; ++v) m_loc = fmaxf(m_loc, s_acc[kb][v]);
+    } else {
+      m_loc = INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m_loc = fminf(m_loc, s_acc[kb][v]);
     }
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) m_loc = fmaxf(m_loc, s_acc[kb][v]);
-    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
+    m_loc = max_with_other_half(m_loc * sc);
     const float m_new = fmaxf(m_run, m_loc);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
     m_run = m_new;
     float psum = 0.f;
-    uint32_t pb[KB][8];  // bf16 pairs: pb[kb][4*s2 + j] = keys (2j, 2j+1) of slab s2
+    uint32_t pb[KB][8];  // bf16 pairs: pb[kb][4*s2 + j] = keys (2j, 2j+1) of 16-key slab s2
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(s_acc[kb][v] - m_new);
-        const float p1 = __builtin_amdgcn_exp2f(s_acc[kb][v + 1] - m_new);
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v], sc, -m_new));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v + 1], sc, -m_new));
         psum += p0 + p1;
         pb[kb][v >> 1] = pack_bf16(p0, p1);
       }
     l_run = l_run * alpha + psum;
+    if (__any(alpha != 1.0f)) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+    }
 
     // ---- O^T += V^T P^T -----------------------------------------------------
     if (has_next) wait_vmem<LOADS_PER_WAVE>(); else wait_vmem<0>();
@@ -258,33 +345,23 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        u32x4 pw = {pb[kb][4 * s2 + 0], pb[kb][4 * s2 + 1], pb[kb][4 * s2 + 2], pb[kb][4 * s2 + 3]};
+        const u32x4 pw = {pb[kb][4 * s2 + 0], pb[kb][4 * s2 + 1], pb[kb][4 * s2 + 2], pb[kb][4 * s2 + 3]};
         const bf16x8 pB = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          u32x2 lo, hi;
-          {
-            const int row = 32 * kb + 16 * s2 + v_row_off;
-            const int cs = (4 * db + v_chunk_off) ^ v_swz<D>(row);
-            lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                                               (LDS_PTR(bf16x4))(ldsV + row * ROWB + cs * 16 + v_byte_off)));
-          }
-          {
-            const int row = 32 * kb + 16 * s2 + 4 + v_row_off;
-            const int cs = (4 * db + v_chunk_off) ^ v_swz<D>(row);
-            hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                                               (LDS_PTR(bf16x4))(ldsV + row * ROWB + cs * 16 + v_byte_off)));
-          }
-          u32x4 aw = {lo[0], lo[1], hi[0], hi[1]};
+          const char *va = ldsV + v_addr[db] + (32 * kb + 16 * s2) * ROWB;
+          const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(va)));
+          const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(va + 4 * ROWB)));
+          const u32x4 aw = {lo[0], lo[1], hi[0], hi[1]};
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pB, o[db], 0, 0, 0);
         }
       }
     __syncthreads();  // every wave is done with the V tile
-    if (has_next) load_tile<D, BK, NT, true>(Vh, c_next * BK, N, ldsV, tid);
+    if (has_next) LoadV::issue(Vres, c_next * BK, ldsV_wave, tid, v_lane_off);
   }
 
   // ---- normalise, stage in LDS, store to the block and its repeat targets ----
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float l_tot = sum_with_other_half(l_run);
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   __syncthreads();
   {
@@ -300,11 +377,11 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
       }
   }
   __syncthreads();
-  const int fbeg = p.fan_ptr[item];
-  const int fend = p.fan_ptr[item + 1];
-  uint16_t *const out_head = p.out + head_off;
+  const int fbeg = fan_ptr[item];
+  const int fend = fan_ptr[item + 1];
+  uint16_t *const out_head = gout + head_off;
   for (int f = fbeg - 1; f < fend; ++f) {
-    const int rd = f < fbeg ? r : p.fan_dst[f];
+    const int rd = f < fbeg ? r : fan_dst[f];
     const int rows_valid = min(BQ, N - rd * BQ);
     uint16_t *dst = out_head + (size_t)rd * BQ * D;
 #pragma unroll 4
@@ -319,12 +396,19 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   }
 }
 
+struct FwdPtrs {
+  const uint16_t *q, *k, *v;
+  uint16_t *out;
+  const int32_t *row_ptr, *col_idx, *work, *fan_ptr, *fan_dst;
+};
+
 template <int D, int BQ, int BK>
-int launch(const FwdParams &p, hipStream_t stream) {
+int launch(const FwdPtrs &a, const FwdDims &p, hipStream_t stream) {
   const long long grid = (long long)p.n_work * p.B;
   if (grid <= 0) return CALIBATT_OK;
   if (grid > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
-  hipLaunchKernelGGL((sparse_attn_fwd_kernel<D, BQ, BK>), dim3((unsigned)grid), dim3(BQ * 2), 0, stream, p);
+  hipLaunchKernelGGL((sparse_attn_fwd_kernel<D, BQ, BK>), dim3((unsigned)grid), dim3(BQ * 2), 0, stream,
+                     a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx, a.work, a.fan_ptr, a.fan_dst, p);
   return hipGetLastError() == hipSuccess ? CALIBATT_OK : CALIBATT_ERR_LAUNCH;
 }
 
@@ -348,16 +432,17 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
     return CALIBATT_ERR_NULL;
   if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
 
-  FwdParams p;
-  p.q = (const uint16_t *)q;
-  p.k = (const uint16_t *)k;
-  p.v = (const uint16_t *)v;
-  p.out = (uint16_t *)out;
-  p.row_ptr = pattern->row_ptr;
-  p.col_idx = pattern->col_idx;
-  p.work = pattern->work;
-  p.fan_ptr = pattern->fan_ptr;
-  p.fan_dst = pattern->fan_dst;
+  FwdPtrs a;
+  a.q = (const uint16_t *)q;
+  a.k = (const uint16_t *)k;
+  a.v = (const uint16_t *)v;
+  a.out = (uint16_t *)out;
+  a.row_ptr = pattern->row_ptr;
+  a.col_idx = pattern->col_idx;
+  a.work = pattern->work;
+  a.fan_ptr = pattern->fan_ptr;
+  a.fan_dst = pattern->fan_dst;
+  FwdDims p;
   p.B = B;
   p.H = H;
   p.N = N;
@@ -367,7 +452,7 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
   p.scale_log2e = scale * 1.4426950408889634f;
   hipStream_t s = (hipStream_t)stream;
 #define CALIBATT_CASE(d, bq, bk) \
-  if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(p, s);
+  if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, s);
   CALIBATT_CASE(128, 128, 128)
   CALIBATT_CASE(128, 128, 64)
   CALIBATT_CASE(128, 64, 128)
