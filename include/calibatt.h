@@ -70,6 +70,7 @@ typedef struct calibatt_pattern {
   const int32_t *work;       /* [n_work] row ids in schedule order */
   const int32_t *fan_ptr;    /* [n_work + 1] offsets into fan_dst, per work item */
   const int32_t *fan_dst;    /* [n_repeat] query blocks that copy work item i, ascending */
+  int32_t *work_counter;     /* NULL, or DEVICE int32[2] workspace, see calibatt_sparse_attn_fwd */
 } calibatt_pattern;
 
 /*
@@ -119,6 +120,16 @@ int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repeat, int H, 
  *          serves every batch index (supplement Section A: one mask for the
  *          conditional and unconditional branch).  Index contents cannot be
  *          validated on the device: build them with calibatt_compile_pattern.
+ *          pattern->work_counter selects how work items reach the GPU:
+ *          NULL  - one workgroup per (computed query block, batch index), in
+ *                  schedule order;
+ *          else  - DEVICE int32[2] owned by the caller, both zero before the
+ *                  first call.  A device-filling set of persistent workgroups
+ *                  pops work items from counter[0] (uneven rows then balance
+ *                  dynamically); the last workgroup to finish sets both words
+ *                  back to zero, so consecutive calls on one stream may share
+ *                  it.  Calls that overlap in time (different streams) need
+ *                  separate counters.  calibatt_compile_pattern sets NULL.
  * scale    multiplies the logits before the softmax (1/sqrt(D) in Eq. 1).
  * stream   hipStream_t (NULL = default stream).  The call only enqueues work.
  *

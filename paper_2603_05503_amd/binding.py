@@ -28,6 +28,7 @@ class _CPattern(C.Structure):
         ("nnz", C.c_int64),
         ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("repeat_src", C.c_void_p),
         ("work", C.c_void_p), ("fan_ptr", C.c_void_p), ("fan_dst", C.c_void_p),
+        ("work_counter", C.c_void_p),
     ]
 
 
@@ -130,8 +131,8 @@ class HostPattern:
     fan_ptr: np.ndarray
     fan_dst: np.ndarray
 
-    def to_device(self, device="cuda") -> "DevicePattern":
-        return DevicePattern(self, device)
+    def to_device(self, device="cuda", persistent=True) -> "DevicePattern":
+        return DevicePattern(self, device, persistent)
 
 
 def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1) -> HostPattern:
@@ -169,7 +170,7 @@ class DevicePattern:
 
     _NAMES = ("row_ptr", "col_idx", "repeat_src", "work", "fan_ptr", "fan_dst")
 
-    def __init__(self, hp: HostPattern, device="cuda"):
+    def __init__(self, hp: HostPattern, device="cuda", persistent=True):
         import torch
 
         self.host = hp
@@ -183,6 +184,9 @@ class DevicePattern:
             setattr(c, f, getattr(hp, f))
         for name in self._NAMES:
             setattr(c, name, self.tensors[name].data_ptr())
+        # int32[2] workspace of the persistent-workgroup scheduler (kept zero between calls)
+        self.counter = torch.zeros(2, dtype=torch.int32, device=device) if persistent else None
+        c.work_counter = self.counter.data_ptr() if persistent else None
         self.c = c
 
     @property

@@ -180,6 +180,7 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
   out->work = work;
   out->fan_ptr = fan_ptr;
   out->fan_dst = fan_dst;
+  out->work_counter = nullptr;
   return CALIBATT_OK;
 }
 

@@ -170,7 +170,7 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
     uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
-    const FwdDims p) {
+    int32_t *counter, const FwdDims p) {
   constexpr int NW = BQ / 32;     // wavefronts per workgroup
   constexpr int NT = NW * 64;     // threads
   constexpr int CH = D / 8;       // 16-byte chunks per row
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   using LoadV = TileLoader<D, BK, NT, true>;
   constexpr int LOADS_PER_WAVE = LoadK::ITERS;  // direct-to-LDS instructions per wave and tile
 
-  __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // LDS_BYTES + 64 (work-item mailbox)
   char *const ldsK = lds;
   char *const ldsV = lds + TILE_BYTES;
 
@@ -195,21 +195,34 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   const int l32 = lane & 31;
   const int g = lane >> 5;
 
-  const int item = blockIdx.x / p.B;
-  const int b = blockIdx.x - item * p.B;
-  const int id = work[item];
-  const int h = id / p.nbq;
-  const int r = id - h * p.nbq;
-  const int N = p.N;
-  const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
-  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
-  const u32x4 Vres = head_rsrc(gv + head_off, (uint32_t)N * ROWB);
   const uint32_t k_lane_off = LoadK::lane_offset(tid, 0);
   const uint32_t v_lane_off = LoadV::lane_offset(tid, 0);
   const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
   const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
   const uint32_t ldsK_wave = lds_base + wave_u * 1024;
   const uint32_t ldsV_wave = ldsK_wave + TILE_BYTES;
+  const int N = p.N;
+  const int n_items = p.n_work * p.B;
+  volatile int *const mailbox = reinterpret_cast<volatile int *>(lds + LDS_BYTES);
+
+  // Persistent workgroups (counter != nullptr): every workgroup pops work items
+  // (schedule order) from one global counter until the list is exhausted, so
+  // uneven rows balance dynamically.  Otherwise: one workgroup per item.
+  for (int wg_item = blockIdx.x;;) {
+  if (counter) {
+    if (tid == 0) *mailbox = atomicAdd(counter, 1);
+    __syncthreads();
+    wg_item = __builtin_amdgcn_readfirstlane(*mailbox);
+  }
+  if (wg_item >= n_items) break;
+  const int item = wg_item / p.B;
+  const int b = wg_item - item * p.B;
+  const int id = work[item];
+  const int h = id / p.nbq;
+  const int r = id - h * p.nbq;
+  const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
+  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
+  const u32x4 Vres = head_rsrc(gv + head_off, (uint32_t)N * ROWB);
 
   const int cbeg = row_ptr[id];
   const int cend = row_ptr[id + 1];
@@ -394,21 +407,62 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
       }
     }
   }
+  if (!counter) break;
+  __syncthreads();  // staging tile fully read before the next item's loads overwrite it
+  }  // work-item loop
+
+  // Last workgroup out re-arms the counter pair for the next launch.
+  if (counter && tid == 0) {
+    __threadfence();
+    if (atomicAdd(counter + 1, 1) == (int)gridDim.x - 1) {
+      counter[0] = 0;
+      counter[1] = 0;
+      __threadfence();
+    }
+  }
 }
 
 struct FwdPtrs {
   const uint16_t *q, *k, *v;
   uint16_t *out;
   const int32_t *row_ptr, *col_idx, *work, *fan_ptr, *fan_dst;
+  int32_t *counter;
 };
 
 template <int D, int BQ, int BK>
 int launch(const FwdPtrs &a, const FwdDims &p, hipStream_t stream) {
-  const long long grid = (long long)p.n_work * p.B;
-  if (grid <= 0) return CALIBATT_OK;
-  if (grid > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
-  hipLaunchKernelGGL((sparse_attn_fwd_kernel<D, BQ, BK>), dim3((unsigned)grid), dim3(BQ * 2), 0, stream,
-                     a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx, a.work, a.fan_ptr, a.fan_dst, p);
+  constexpr int TILE_BYTES = BK * D * 2;
+  constexpr int OST = D * 2 + 16;
+  constexpr int LDS_BYTES = (2 * TILE_BYTES > BQ * OST) ? 2 * TILE_BYTES : BQ * OST;
+  constexpr int SMEM = LDS_BYTES + 64;
+  const long long items = (long long)p.n_work * p.B;
+  if (items <= 0) return CALIBATT_OK;
+  if (items > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
+  auto kernel = sparse_attn_fwd_kernel<D, BQ, BK>;
+
+  // Per-device launch facts, looked up once per instantiation and device.
+  struct DevInfo {
+    bool ready = false;
+    int slots = 0;  // co-resident workgroups on the whole device
+  };
+  static DevInfo info[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CALIBATT_ERR_LAUNCH;
+  if (!info[dev].ready) {
+    int cus = 0, per_cu = 0;
+    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kernel, BQ * 2, SMEM) != hipSuccess ||
+        cus <= 0 || per_cu <= 0)
+      return CALIBATT_ERR_LAUNCH;
+    info[dev].slots = cus * per_cu;
+    info[dev].ready = true;
+  }
+  long long grid = items;
+  int32_t *counter = a.counter;
+  if (counter && items > info[dev].slots) grid = info[dev].slots; else counter = nullptr;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(BQ * 2), SMEM, stream, a.q, a.k, a.v, a.out, a.row_ptr,
+                     a.col_idx, a.work, a.fan_ptr, a.fan_dst, counter, p);
   return hipGetLastError() == hipSuccess ? CALIBATT_OK : CALIBATT_ERR_LAUNCH;
 }
 
@@ -442,6 +496,7 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
   a.work = pattern->work;
   a.fan_ptr = pattern->fan_ptr;
   a.fan_dst = pattern->fan_dst;
+  a.counter = pattern->work_counter;
   FwdDims p;
   p.B = B;
   p.H = H;
