@@ -291,13 +291,33 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     __syncthreads();
     f32x16 s_acc[KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.f;
+    // k-slab outer, key sub-block inner: consecutive MFMAs hit different
+    // accumulators; the A operands of slab s+1 are read while slab s multiplies.
+    {
+      bf16x8 ka[2][KB];
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+        ka[0][kb] = *reinterpret_cast<const bf16x8 *>(ldsK + (k_addr0 + kb * 32 * ROWB));
 #pragma unroll
       for (int s = 0; s < DS; ++s) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ldsK + ((k_addr0 ^ (s << 5)) + kb * 32 * ROWB));
-        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], s_acc[kb], 0, 0, 0);
+        if (s + 1 < DS) {
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+            ka[(s + 1) & 1][kb] =
+                *reinterpret_cast<const bf16x8 *>(ldsK + ((k_addr0 ^ ((s + 1) << 5)) + kb * 32 * ROWB));
+        }
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+          s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][kb], qreg[s], s_acc[kb], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab 0
+#pragma unroll
+      for (int s = 0; s < DS; ++s) {
+        if (s + 1 < DS) __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab s+1
+        __builtin_amdgcn_sched_group_barrier(0x008, KB, 0);                  // MFMAs of slab s
       }
     }
     __syncthreads();  // every wave is done with the K tile
@@ -332,16 +352,25 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     const float m_new = fmaxf(m_run, m_loc);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
     m_run = m_new;
+    // P = exp2(sc * S - m) rounded to bf16 pairs; the row sum is taken over the
+    // rounded values (two per v_dot2c with a vector of ones), so numerator and
+    // denominator of the final division see the same probabilities.
     float psum = 0.f;
     uint32_t pb[KB][8];  // bf16 pairs: pb[kb][4*s2 + j] = keys (2j, 2j+1) of 16-key slab s2
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
+#ifdef CALIBATT_DEBUG_NO_EXP
+        const float p0 = s_acc[kb][v], p1 = s_acc[kb][v + 1];
+#else
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v], sc, -m_new));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v + 1], sc, -m_new));
-        psum += p0 + p1;
-        pb[kb][v >> 1] = pack_bf16(p0, p1);
+#endif
+        const uint32_t pk = pack_bf16(p0, p1);
+        pb[kb][v >> 1] = pk;
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, psum, false);
       }
     l_run = l_run * alpha + psum;
     if (__any(alpha != 1.0f)) {
@@ -354,21 +383,37 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     // ---- O^T += V^T P^T -----------------------------------------------------
     if (has_next) wait_vmem<LOADS_PER_WAVE>(); else wait_vmem<0>();
     __syncthreads();
+    {
+      // 16-key slab j = 2 kb + s2: V^T operands of slab j+1 are read while slab j multiplies
+      u32x4 va[2][DB];
+      auto v_read = [&](int j, int st) {
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
+        for (int db = 0; db < DB; ++db) {
+          const char *a = ldsV + v_addr[db] + 16 * j * ROWB;
+          const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(a)));
+          const u32x2 hi =
+              __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(a + 4 * ROWB)));
+          va[st][db] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+        }
+      };
+      v_read(0, 0);
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
+      for (int j = 0; j < 2 * KB; ++j) {
+        if (j + 1 < 2 * KB) v_read(j + 1, (j + 1) & 1);
+        const int kb = j >> 1, s2 = j & 1;
         const u32x4 pw = {pb[kb][4 * s2 + 0], pb[kb][4 * s2 + 1], pb[kb][4 * s2 + 2], pb[kb][4 * s2 + 3]};
         const bf16x8 pB = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const char *va = ldsV + v_addr[db] + (32 * kb + 16 * s2) * ROWB;
-          const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(va)));
-          const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(va + 4 * ROWB)));
-          const u32x4 aw = {lo[0], lo[1], hi[0], hi[1]};
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pB, o[db], 0, 0, 0);
-        }
+        for (int db = 0; db < DB; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[j & 1][db]), pB, o[db], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
+#pragma unroll
+      for (int j = 0; j < 2 * KB; ++j) {
+        if (j + 1 < 2 * KB) __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
+      }
+    }
     __syncthreads();  // every wave is done with the V tile
     if (has_next) LoadV::issue(Vres, c_next * BK, ldsV_wave, tid, v_lane_off);
   }
