@@ -324,18 +324,21 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     if (has_next) LoadK::issue(Kres, c_next * BK, ldsK_wave, tid, k_lane_off);
 
     // ---- online softmax (log2 domain) ----------------------------------------
-    if (c == p.nbk - 1 && (N % BK) != 0) {  // keys >= N of the ragged last block
+    float sc_t = sc;  // multiplier still to be applied to s_acc
+    if (c == p.nbk - 1 && (N % BK) != 0) {
+      // ragged last block: scale now, put keys >= N at -inf, continue with multiplier 1
       const int key0 = c * BK + 8 * g;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
-          if (key >= N) s_acc[kb][v] = sc >= 0.f ? -INFINITY : INFINITY;
+          s_acc[kb][v] = key < N ? s_acc[kb][v] * sc : -INFINITY;
         }
+      sc_t = 1.0f;
     }
     float m_loc;
-    if (sc >= 0.f) {
+    if (sc_t >= 0.f) {
       m_loc = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
@@ -348,7 +351,7 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
 #pragma unroll
         for (int v = 0; v < 16; ++v) m_loc = fminf(m_loc, s_acc[kb][v]);
     }
-    m_loc = max_with_other_half(m_loc * sc);
+    m_loc = max_with_other_half(m_loc * sc_t);
     const float m_new = fmaxf(m_run, m_loc);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
     m_run = m_new;
@@ -365,8 +368,8 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
 #ifdef CALIBATT_DEBUG_NO_EXP
         const float p0 = s_acc[kb][v], p1 = s_acc[kb][v + 1];
 #else
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v], sc, -m_new));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v + 1], sc, -m_new));
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v], sc_t, -m_new));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v + 1], sc_t, -m_new));
 #endif
         const uint32_t pk = pack_bf16(p0, p1);
         pb[kb][v >> 1] = pk;

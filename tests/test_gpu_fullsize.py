@@ -1,0 +1,69 @@
+"""Parity at the benchmark's full shapes, in the launch configuration bench.py
+times: a seeded sample of query blocks against the oracle (computed block by
+block), every repeated block bitwise against its source, and a second run that
+must reproduce the first bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import sparse_attention_blocks
+from tests.parity_utils import MAX_ABS, MEAN_ABS, assert_repeats_bitwise, bits_to_f64, from_dev, to_dev
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_items(wl, rng, per_stratum=6):
+    """Query blocks stratified by kept count (shortest, quartiles, longest), the
+    ragged last block, a few repeated blocks."""
+    items = []
+    cnt = wl.mask.astype(bool).sum(axis=2)
+    heads = rng.choice(wl.H, size=min(3, wl.H), replace=False)
+    for h in heads:
+        live = np.flatnonzero(wl.repeat[h] < 0)
+        order = live[np.argsort(cnt[h, live], kind="stable")]
+        for r in order[np.linspace(0, order.size - 1, per_stratum).astype(int)]:
+            items.append((0, int(h), int(r)))
+        items.append((0, int(h), wl.nbq - 1))
+        rep = np.flatnonzero(wl.repeat[h] >= 0)
+        if rep.size:
+            items.append((0, int(h), int(rep[rng.integers(rep.size)])))
+    return sorted(set(items))
+
+
+@pytest.mark.parametrize("name,density", [("wan480", None), ("mochi", None), ("wan720", 0.15)])
+def test_fullsize_sampled_parity(lib, name, density):
+    import torch
+
+    print(f"full size {name}", flush=True)
+    wl = make_workload(name, density=density)
+    hp = lib.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, 1)
+    dp = hp.to_device()
+    q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
+    out = torch.empty_like(q)
+    out.view(torch.int16).fill_(0x7FC1)
+    lib.sparse_attn_fwd(q, k, v, out, dp, wl.scale)
+    torch.cuda.synchronize()
+    got = from_dev(out)
+    assert np.isfinite(bits_to_f64(got[:, :1])).all()
+    out2 = torch.empty_like(q)
+    lib.sparse_attn_fwd(q, k, v, out2, dp, wl.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "run-to-run difference"
+    assert_repeats_bitwise(got, wl.repeat, wl.block_q, wl.N)
+
+    rng = np.random.default_rng(99)
+    items = _sample_items(wl, rng)
+    want = sparse_attention_blocks(wl.q, wl.k, wl.v, wl.mask, wl.repeat, wl.scale, wl.block_q, wl.block_k, items)
+    worst, total, n = 0.0, 0.0, 0
+    num = den = 0.0
+    for (b, h, r), w in zip(items, want):
+        g = bits_to_f64(got[b, h, r * wl.block_q : r * wl.block_q + w.shape[0]])
+        d = np.abs(g - w)
+        worst = max(worst, float(d.max()))
+        total += float(d.sum())
+        n += d.size
+        num += float((d ** 2).sum())
+        den += float((w ** 2).sum())
+    print(f"{name}: {len(items)} blocks, max_abs {worst:.3e}, mean_abs {total / n:.3e}, rel_l2 {np.sqrt(num / den):.3e}", flush=True)
+    assert worst <= MAX_ABS and total / n <= MEAN_ABS
+    assert np.sqrt(num / den) < 2e-2
