@@ -33,11 +33,15 @@ def parse_args():
     ap.add_argument("--workload", default="wan480", choices=["tiny", "wan480", "wan720", "mochi"])
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--repeat-frac", type=float, default=None)
-    ap.add_argument("--order", type=int, default=1)
+    ap.add_argument("--order", type=int, default=3)
     ap.add_argument("--heads", type=int, default=None)
     ap.add_argument("--no-dense", action="store_true", help="skip the all-ones reference run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--cpu-blocks", type=int, default=48, help="query blocks in the CPU oracle sample")
+    ap.add_argument("--cpu-blocks", type=int, default=640, help="query blocks in the CPU oracle sample")
+    ap.add_argument("--no-persistent", action="store_true", help="one workgroup per work item instead of persistent workgroups")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one elementwise kernel that reads and writes 1 GiB each (reference for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -124,7 +128,7 @@ def main():
     t0 = time.perf_counter()
     hp = pkg.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, args.order)
     compile_ms = (time.perf_counter() - t0) * 1e3
-    dp = hp.to_device()
+    dp = hp.to_device(persistent=not args.no_persistent)
     q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
     out = torch.empty_like(q)
     tile_flops = 4.0 * wl.block_q * wl.block_k * wl.D
@@ -134,10 +138,17 @@ def main():
     value = flops / (wall_ms * 1e-3) / 1e12
     achieved = flops / (ev_mean_ms * 1e-3) / 1e12
 
+    if args.calibrate_copy:
+        a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")  # 1 GiB
+        b = torch.empty_like(a)
+        torch.add(a, 1, out=b)
+        torch.cuda.synchronize()
+        del a, b
+
     dense = None
     if not args.no_dense:
         wd = make_workload(args.workload, dense=True, with_qkv=False, heads=args.heads)
-        hd = pkg.compile_pattern(wd.mask, wd.repeat, wd.H, wd.N, wd.block_q, wd.block_k, args.order).to_device()
+        hd = pkg.compile_pattern(wd.mask, wd.repeat, wd.H, wd.N, wd.block_q, wd.block_k, args.order).to_device(persistent=not args.no_persistent)
         d_wall, d_ev, d_med = time_launches(pkg, torch, q, k, v, out, hd, wl.scale, max(3, args.steps // 4), 1)
         dense = {"ms": d_ev, "tflops": hd.nnz * wl.B * tile_flops / (d_ev * 1e-3) / 1e12,
                  "speedup_sparse_vs_dense": d_ev / ev_mean_ms}
@@ -162,6 +173,7 @@ def main():
             "computed_rows": int(hp.n_work),
             "repeated_rows": int(hp.n_repeat),
             "schedule_order": args.order,
+            "persistent_workgroups": not args.no_persistent,
             "pattern_compile_ms": compile_ms,
         },
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,

@@ -43,8 +43,16 @@ typedef enum calibatt_status {
 enum {
   CALIBATT_ORDER_NATURAL = 0,   /* (h, r) ascending */
   CALIBATT_ORDER_LONGEST = 1,   /* kept count descending, then h, then r */
-  CALIBATT_ORDER_HEAD_LONGEST = 2 /* h ascending, then kept count descending, then r */
+  CALIBATT_ORDER_HEAD_LONGEST = 2, /* h ascending, then kept count descending, then r */
+  CALIBATT_ORDER_XCD_HEADS = 3 /* heads dealt to CALIBATT_GROUPS groups (one per XCD, each XCD has its
+                                  own L2): heads by total kept blocks descending (then h), each to the
+                                  group with the smallest load so far (then lowest group).  A group's
+                                  segment of work lists first its long blocks (2*count*n_work > 3*nnz)
+                                  by count descending, then dealing order of the head, then r; then the
+                                  other blocks head by head in dealing order, r ascending.  Segments
+                                  follow each other in group order. */
 };
+#define CALIBATT_GROUPS 8
 
 /*
  * Compiled pattern: plain data, all pointers BORROWED (never freed by the
@@ -70,7 +78,9 @@ typedef struct calibatt_pattern {
   const int32_t *work;       /* [n_work] row ids in schedule order */
   const int32_t *fan_ptr;    /* [n_work + 1] offsets into fan_dst, per work item */
   const int32_t *fan_dst;    /* [n_repeat] query blocks that copy work item i, ascending */
-  int32_t *work_counter;     /* NULL, or DEVICE int32[2] workspace, see calibatt_sparse_attn_fwd */
+  int32_t *work_counter;     /* NULL, or DEVICE int32[16] workspace, see calibatt_sparse_attn_fwd */
+  int32_t n_groups;          /* 1, or CALIBATT_GROUPS for CALIBATT_ORDER_XCD_HEADS */
+  int32_t group_ptr[CALIBATT_GROUPS + 1]; /* segment g of `work` is [group_ptr[g], group_ptr[g+1]) */
 } calibatt_pattern;
 
 /*
@@ -95,6 +105,7 @@ int calibatt_pattern_sizes(const uint8_t *mask, const int32_t *repeat, int H, in
  *   col_idx    [col_cap]    first nnz entries written; needs col_cap >= nnz
  *   repeat_src [H*nbq]
  *   work       [H*nbq]      first n_work entries written, order per `order`
+ *                           (out->n_groups / out->group_ptr describe its segments)
  *   fan_ptr    [H*nbq + 1]  first n_work + 1 entries written
  *   fan_dst    [H*nbq]      first n_repeat entries written
  * `out` receives the dimensions, counts and the six host pointers.
@@ -123,13 +134,17 @@ int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repeat, int H, 
  *          pattern->work_counter selects how work items reach the GPU:
  *          NULL  - one workgroup per (computed query block, batch index), in
  *                  schedule order;
- *          else  - DEVICE int32[2] owned by the caller, both zero before the
+ *          else  - DEVICE int32[16] owned by the caller, all zero before the
  *                  first call.  A device-filling set of persistent workgroups
- *                  pops work items from counter[0] (uneven rows then balance
- *                  dynamically); the last workgroup to finish sets both words
- *                  back to zero, so consecutive calls on one stream may share
- *                  it.  Calls that overlap in time (different streams) need
- *                  separate counters.  calibatt_compile_pattern sets NULL.
+ *                  pops work items from one counter per group (uneven rows
+ *                  then balance dynamically).  With n_groups ==
+ *                  CALIBATT_GROUPS a workgroup first drains the group of the
+ *                  XCD it runs on - the heads of one group then share that
+ *                  XCD's L2 - and steals from the other groups afterwards.
+ *                  The last workgroup to finish sets all words back to zero,
+ *                  so consecutive calls on one stream may share the workspace.
+ *                  Calls that overlap in time (different streams) need
+ *                  separate workspaces.  calibatt_compile_pattern sets NULL.
  * scale    multiplies the logits before the softmax (1/sqrt(D) in Eq. 1).
  * stream   hipStream_t (NULL = default stream).  The call only enqueues work.
  *

@@ -19,7 +19,20 @@ repeat_src[H*nbq]   -1, or the source block (same head).
 work[n_work]        ids h*nbq + r of the non-repeated blocks in schedule order:
                     order 0: (h, r) ascending;
                     order 1: kept count descending, then h, then r;
-                    order 2: h ascending, then kept count descending, then r.
+                    order 2: h ascending, then kept count descending, then r;
+                    order 3: heads are dealt to N_GROUPS = 8 groups (one per
+                             XCD of the target GPU): heads sorted by total kept
+                             blocks descending (then h), each given to the group
+                             with the smallest load so far (then lowest group);
+                             a group's segment of work first lists its "long"
+                             blocks (kept count > 1.5 x the mean over all
+                             computed blocks, i.e. 2*count*n_work > 3*nnz) by
+                             count descending, then dealing order of the head,
+                             then r; after them the remaining blocks head by
+                             head in dealing order, r ascending.  Group 0's
+                             segment comes first, then group 1, ...
+group_ptr[9]        order 3: start of each group's segment in work, last entry
+                    n_work.  Other orders: one group, [0, n_work, n_work, ...].
 fan_ptr[n_work+1], fan_dst[n_repeat]
                     for work item i the ascending list of blocks r' of the same
                     head with repeat[h, r'] == r.
@@ -32,6 +45,9 @@ Rejected inputs (exceptions here, status codes in the library):
 from __future__ import annotations
 
 import numpy as np
+
+
+N_GROUPS = 8
 
 
 class PatternError(ValueError):
@@ -82,7 +98,7 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
     """Returns a dict of int32 arrays: row_ptr, col_idx, repeat_src, work,
     fan_ptr, fan_dst, plus ints nbq, nbk, nnz, n_work, n_repeat."""
     nbq, nbk = _dims(H, N, block_q, block_k)
-    if order not in (0, 1, 2):
+    if order not in (0, 1, 2, 3):
         raise PatternError("unsupported", f"order={order}")
     mask = np.asarray(mask).reshape(H, nbq, nbk)
     rep = np.full((H, nbq), -1, dtype=np.int64) if repeat is None else np.asarray(repeat, dtype=np.int64).reshape(H, nbq)
@@ -103,6 +119,25 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
         items.sort(key=lambda hr: (-counts[hr], hr[0], hr[1]))
     elif order == 2:
         items.sort(key=lambda hr: (hr[0], -counts[hr], hr[1]))
+    group_ptr = [0] + [len(items)] * N_GROUPS
+    if order == 3:
+        weight = [sum(counts[(h, r)] for r in range(nbq)) for h in range(H)]
+        load = [0] * N_GROUPS
+        members = [[] for _ in range(N_GROUPS)]
+        for h in sorted(range(H), key=lambda h: (-weight[h], h)):
+            g = min(range(N_GROUPS), key=lambda g: (load[g], g))
+            members[g].append(h)
+            load[g] += weight[h]
+        items = []
+        group_ptr = [0]
+        nnz_total, n_live = len(col_idx), sum(1 for h in range(H) for r in range(nbq) if rep[h, r] < 0)
+        is_long = lambda hr: 2 * counts[hr] * n_live > 3 * nnz_total
+        for g in range(N_GROUPS):
+            live = [(h, r) for h in members[g] for r in range(nbq) if rep[h, r] < 0]
+            rank = {h: i for i, h in enumerate(members[g])}
+            items.extend(sorted((hr for hr in live if is_long(hr)), key=lambda hr: (-counts[hr], rank[hr[0]], hr[1])))
+            items.extend(hr for hr in live if not is_long(hr))
+            group_ptr.append(len(items))
     work = [h * nbq + r for (h, r) in items]
 
     fan_ptr = [0]
@@ -116,4 +151,5 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
         nbq=nbq, nbk=nbk, nnz=len(col_idx), n_work=len(work), n_repeat=len(fan_dst),
         row_ptr=i32(row_ptr), col_idx=i32(col_idx), repeat_src=i32(rep),
         work=i32(work), fan_ptr=i32(fan_ptr), fan_dst=i32(fan_dst),
+        n_groups=N_GROUPS if order == 3 else 1, group_ptr=i32(group_ptr),
     )

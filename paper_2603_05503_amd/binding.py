@@ -29,6 +29,8 @@ class _CPattern(C.Structure):
         ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("repeat_src", C.c_void_p),
         ("work", C.c_void_p), ("fan_ptr", C.c_void_p), ("fan_dst", C.c_void_p),
         ("work_counter", C.c_void_p),
+        ("n_groups", C.c_int32),
+        ("group_ptr", C.c_int32 * 9),
     ]
 
 
@@ -130,6 +132,8 @@ class HostPattern:
     work: np.ndarray
     fan_ptr: np.ndarray
     fan_dst: np.ndarray
+    n_groups: int = 1
+    group_ptr: Optional[np.ndarray] = None
 
     def to_device(self, device="cuda", persistent=True) -> "DevicePattern":
         return DevicePattern(self, device, persistent)
@@ -161,6 +165,7 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1) -> HostPatter
         n_work=cp.n_work, n_repeat=cp.n_repeat, order=cp.order, max_row=cp.max_row, nnz=cp.nnz,
         row_ptr=row_ptr, col_idx=col_idx[:nnz], repeat_src=repeat_src,
         work=work[: cp.n_work], fan_ptr=fan_ptr[: cp.n_work + 1], fan_dst=fan_dst[: cp.n_repeat],
+        n_groups=cp.n_groups, group_ptr=np.array(list(cp.group_ptr), dtype=np.int32),
     )
 
 
@@ -184,9 +189,13 @@ class DevicePattern:
             setattr(c, f, getattr(hp, f))
         for name in self._NAMES:
             setattr(c, name, self.tensors[name].data_ptr())
-        # int32[2] workspace of the persistent-workgroup scheduler (kept zero between calls)
-        self.counter = torch.zeros(2, dtype=torch.int32, device=device) if persistent else None
+        # int32[16] workspace of the persistent-workgroup scheduler (kept zero between calls)
+        self.counter = torch.zeros(16, dtype=torch.int32, device=device) if persistent else None
         c.work_counter = self.counter.data_ptr() if persistent else None
+        c.n_groups = hp.n_groups
+        gp = hp.group_ptr if hp.group_ptr is not None else np.array([0] + [hp.n_work] * 8, np.int32)
+        for i in range(9):
+            c.group_ptr[i] = int(gp[i])
         self.c = c
 
     @property

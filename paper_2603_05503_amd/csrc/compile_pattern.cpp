@@ -10,8 +10,10 @@
 // pattern costs O(H*nbq*nbk) byte reads plus O(H*nbq + nbk) bookkeeping.
 #include "calibatt.h"
 
+#include <algorithm>
 #include <cstring>
 #include <new>
+#include <numeric>
 #include <vector>
 
 namespace {
@@ -86,7 +88,7 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
                                         calibatt_pattern *out) {
   if (!mask || !row_ptr || !col_idx || !repeat_src || !work || !fan_ptr || !fan_dst || !out)
     return CALIBATT_ERR_NULL;
-  if (order < CALIBATT_ORDER_NATURAL || order > CALIBATT_ORDER_HEAD_LONGEST)
+  if (order < CALIBATT_ORDER_NATURAL || order > CALIBATT_ORDER_XCD_HEADS)
     return CALIBATT_ERR_UNSUPPORTED;
   Dims d;
   int st = make_dims(H, N, block_q, block_k, d);
@@ -121,11 +123,54 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
 
   // Schedule.  A stable counting sort on (nbk - count) keeps (h, r) ascending
   // inside one count; per head for order 2, over all rows for order 1.
+  int32_t group_ptr[CALIBATT_GROUPS + 1];
+  group_ptr[0] = 0;
+  for (int g = 1; g <= CALIBATT_GROUPS; ++g) group_ptr[g] = n_work;
   try {
     if (order == CALIBATT_ORDER_NATURAL) {
       int32_t w = 0;
       for (int64_t i = 0; i < d.rows; ++i)
         if (repeat_src[i] < 0) work[w++] = (int32_t)i;
+    } else if (order == CALIBATT_ORDER_XCD_HEADS) {
+      // Deal heads, heaviest first, to the currently lightest group.
+      std::vector<int64_t> weight((size_t)H);
+      for (int h = 0; h < H; ++h)
+        weight[(size_t)h] = (int64_t)row_ptr[(int64_t)(h + 1) * d.nbq] - row_ptr[(int64_t)h * d.nbq];
+      std::vector<int> heads((size_t)H);
+      std::iota(heads.begin(), heads.end(), 0);
+      std::stable_sort(heads.begin(), heads.end(),
+                       [&](int a, int b) { return weight[(size_t)a] > weight[(size_t)b]; });
+      int64_t load[CALIBATT_GROUPS] = {0};
+      std::vector<int> members[CALIBATT_GROUPS];
+      for (int h : heads) {
+        int best = 0;
+        for (int g = 1; g < CALIBATT_GROUPS; ++g)
+          if (load[g] < load[best]) best = g;
+        members[best].push_back(h);
+        load[best] += weight[(size_t)h];
+      }
+      // Per group: long rows first (longest first), then head by head.
+      int32_t w = 0;
+      std::vector<int32_t> longs;
+      auto is_long = [&](int64_t i) {
+        return 2 * (int64_t)(row_ptr[i + 1] - row_ptr[i]) * n_work > 3 * nnz;
+      };
+      for (int g = 0; g < CALIBATT_GROUPS; ++g) {
+        group_ptr[g] = w;
+        longs.clear();
+        for (int h : members[g])
+          for (int64_t i = (int64_t)h * d.nbq; i < (int64_t)(h + 1) * d.nbq; ++i)
+            if (repeat_src[i] < 0 && is_long(i)) longs.push_back((int32_t)i);
+        // longs is in (dealing order, r) order; a stable sort by count keeps that for ties
+        std::stable_sort(longs.begin(), longs.end(), [&](int32_t a, int32_t b) {
+          return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
+        });
+        for (int32_t i : longs) work[w++] = i;
+        for (int h : members[g])
+          for (int64_t i = (int64_t)h * d.nbq; i < (int64_t)(h + 1) * d.nbq; ++i)
+            if (repeat_src[i] < 0 && !is_long(i)) work[w++] = (int32_t)i;
+      }
+      group_ptr[CALIBATT_GROUPS] = w;
     } else {
       std::vector<int32_t> bucket((size_t)d.nbk + 2);
       const int64_t span = order == CALIBATT_ORDER_LONGEST ? d.rows : d.nbq;
@@ -181,6 +226,8 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
   out->fan_ptr = fan_ptr;
   out->fan_dst = fan_dst;
   out->work_counter = nullptr;
+  out->n_groups = order == CALIBATT_ORDER_XCD_HEADS ? CALIBATT_GROUPS : 1;
+  for (int g = 0; g <= CALIBATT_GROUPS; ++g) out->group_ptr[g] = group_ptr[g];
   return CALIBATT_OK;
 }
 

@@ -47,6 +47,8 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 struct FwdDims {
   int B, H, N, nbq, nbk, n_work;
   float scale_log2e;
+  int n_groups;                         // segments of the work list (1, or one per XCD)
+  int group_ptr[CALIBATT_GROUPS + 1];   // segment g = work[group_ptr[g] .. group_ptr[g+1])
 };
 
 template <int N_OUTSTANDING>
@@ -205,19 +207,46 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   const int n_items = p.n_work * p.B;
   volatile int *const mailbox = reinterpret_cast<volatile int *>(lds + LDS_BYTES);
 
-  // Persistent workgroups (counter != nullptr): every workgroup pops work items
-  // (schedule order) from one global counter until the list is exhausted, so
-  // uneven rows balance dynamically.  Otherwise: one workgroup per item.
+  // Persistent workgroups (counter != nullptr): every workgroup pops (work item,
+  // batch index) pairs from per-group counters until all groups are drained, so
+  // uneven rows balance dynamically.  With one group per XCD a workgroup starts
+  // on the group of the XCD it runs on (the heads of a group then share that
+  // XCD's L2) and moves on to the next group, for good, once one is empty.
+  // Otherwise: one workgroup per pair.
+#ifdef CALIBATT_DEBUG_TIMING
+  const long long dbg_t0 = wall_clock64();
+  int dbg_items = 0, dbg_tiles = 0;
+#endif
+  int cur_group = 0, groups_left = p.n_groups;
+  if (counter && p.n_groups > 1)
+    cur_group = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) % p.n_groups;  // HW_REG_XCC_ID[3:0]
   for (int wg_item = blockIdx.x;;) {
   if (counter) {
-    if (tid == 0) *mailbox = atomicAdd(counter, 1);
+    if (tid == 0) {
+      int found = -1;
+      while (groups_left > 0) {
+        const int it = atomicAdd(counter + cur_group, 1);
+        if (it < (p.group_ptr[cur_group + 1] - p.group_ptr[cur_group]) * p.B) {
+          found = p.group_ptr[cur_group] * p.B + it;
+          break;
+        }
+        cur_group = cur_group + 1 == p.n_groups ? 0 : cur_group + 1;
+        --groups_left;
+      }
+      *mailbox = found;
+    }
     __syncthreads();
     wg_item = __builtin_amdgcn_readfirstlane(*mailbox);
+    if (wg_item < 0) break;
   }
   if (wg_item >= n_items) break;
   const int item = wg_item / p.B;
   const int b = wg_item - item * p.B;
   const int id = work[item];
+#ifdef CALIBATT_DEBUG_TIMING
+  ++dbg_items;
+  dbg_tiles += row_ptr[id + 1] - row_ptr[id];
+#endif
   const int h = id / p.nbq;
   const int r = id - h * p.nbq;
   const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
@@ -459,12 +488,20 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   __syncthreads();  // staging tile fully read before the next item's loads overwrite it
   }  // work-item loop
 
+#ifdef CALIBATT_DEBUG_TIMING
+  if (counter && tid == 0) {
+    long long *dbg = reinterpret_cast<long long *>(counter + 32) + 4 * blockIdx.x;
+    dbg[0] = dbg_t0;
+    dbg[1] = wall_clock64();
+    dbg[2] = dbg_items;
+    dbg[3] = dbg_tiles | ((long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) << 32);
+  }
+#endif
   // Last workgroup out re-arms the counter pair for the next launch.
   if (counter && tid == 0) {
     __threadfence();
-    if (atomicAdd(counter + 1, 1) == (int)gridDim.x - 1) {
-      counter[0] = 0;
-      counter[1] = 0;
+    if (atomicAdd(counter + CALIBATT_GROUPS, 1) == (int)gridDim.x - 1) {
+      for (int i = 0; i <= CALIBATT_GROUPS; ++i) counter[i] = 0;
       __threadfence();
     }
   }
@@ -529,6 +566,11 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
       pattern->nbq != nbq || pattern->nbk != nbk || pattern->n_work < 0 || pattern->n_repeat < 0 ||
       (int64_t)pattern->n_work + pattern->n_repeat != (int64_t)H * nbq)
     return CALIBATT_ERR_PATTERN_MISMATCH;
+  if (pattern->n_groups != 1 && pattern->n_groups != CALIBATT_GROUPS) return CALIBATT_ERR_PATTERN_MISMATCH;
+  if (pattern->group_ptr[0] != 0 || pattern->group_ptr[pattern->n_groups] != pattern->n_work)
+    return CALIBATT_ERR_PATTERN_MISMATCH;
+  for (int g = 0; g < pattern->n_groups; ++g)
+    if (pattern->group_ptr[g] > pattern->group_ptr[g + 1]) return CALIBATT_ERR_PATTERN_MISMATCH;
   if (!pattern->row_ptr || !pattern->work || !pattern->fan_ptr ||
       (pattern->nnz > 0 && !pattern->col_idx) || (pattern->n_repeat > 0 && !pattern->fan_dst))
     return CALIBATT_ERR_NULL;
@@ -553,6 +595,8 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
   p.nbk = nbk;
   p.n_work = pattern->n_work;
   p.scale_log2e = scale * 1.4426950408889634f;
+  p.n_groups = pattern->n_groups;
+  for (int g = 0; g <= CALIBATT_GROUPS; ++g) p.group_ptr[g] = pattern->group_ptr[g];
   hipStream_t s = (hipStream_t)stream;
 #define CALIBATT_CASE(d, bq, bk) \
   if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, s);

@@ -23,7 +23,8 @@ KIND_TO_STATUS = {"range": -4, "chain": -5, "tail": -6}
 def _lib_compile(mask, repeat, H, N, bq, bk, order):
     hp = pkg.compile_pattern(mask, repeat, H, N, bq, bk, order)
     d = {name: getattr(hp, name) for name in ARRAYS}
-    d.update(nnz=hp.nnz, n_work=hp.n_work, n_repeat=hp.n_repeat, nbq=hp.nbq, nbk=hp.nbk, max_row=hp.max_row)
+    d.update(nnz=hp.nnz, n_work=hp.n_work, n_repeat=hp.n_repeat, nbq=hp.nbq, nbk=hp.nbk, max_row=hp.max_row,
+             n_groups=hp.n_groups, group_ptr=hp.group_ptr)
     return d
 
 
@@ -31,8 +32,9 @@ def _assert_equal(a, b):
     for name in ARRAYS:
         assert a[name].dtype == np.int32
         assert np.array_equal(a[name], b[name]), name
-    for name in ("nnz", "n_work", "n_repeat", "nbq", "nbk"):
+    for name in ("nnz", "n_work", "n_repeat", "nbq", "nbk", "n_groups"):
         assert a[name] == b[name], name
+    assert a["group_ptr"].tolist() == b["group_ptr"].tolist()
 
 
 def test_header_symbols_exported():
@@ -63,7 +65,7 @@ def test_library_matches_oracle_random(seed):
     mask = mask * rng.integers(1, 255, size=mask.shape).astype(np.uint8)
     if seed % 5 == 0:
         repeat = None
-    for order in (0, 1, 2):
+    for order in (0, 1, 2, 3):
         a = _lib_compile(mask, repeat, H, N, bq, bk, order)
         b = oracle_compile(mask, repeat, H, N, bq, bk, order)
         _assert_equal(a, b)
@@ -74,8 +76,8 @@ def test_library_matches_oracle_random(seed):
 
 @pytest.mark.parametrize("name", ["tiny", "wan480", "mochi"])
 def test_library_matches_oracle_named_configs(name):
-    wl = make_workload(name, with_qkv=False, heads=None if name == "tiny" else 3)
-    for order in (0, 1, 2):
+    wl = make_workload(name, with_qkv=False, heads=None if name == "tiny" else 11)
+    for order in (0, 1, 2, 3):
         a = _lib_compile(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, order)
         b = oracle_compile(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, order)
         _assert_equal(a, b)
@@ -115,6 +117,7 @@ def test_library_error_codes_raw_abi():
     assert lib.calibatt_pattern_sizes(m, None, 0, 32, 8, 8, None, None, None) == -2
     assert lib.calibatt_pattern_sizes(m, None, 1, 32, 8, 8, None, None, None) == 0
     # forward: argument validation happens on the host before any GPU call
+    assert cp.n_groups == 1 and list(cp.group_ptr)[:2] == [0, 4]
     cp.H, cp.N, cp.block_q, cp.block_k = 1, 32, 8, 8
     one = ctypes.c_void_p(16)
     fwd = lib.calibatt_sparse_attn_fwd

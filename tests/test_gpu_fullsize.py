@@ -36,7 +36,7 @@ def test_fullsize_sampled_parity(lib, name, density):
 
     print(f"full size {name}", flush=True)
     wl = make_workload(name, density=density)
-    hp = lib.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, 1)
+    hp = lib.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, 3)
     dp = hp.to_device()
     q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
     out = torch.empty_like(q)

@@ -43,17 +43,40 @@ def independent_numpy_compile(mask, repeat, H, N, bq, bk, order):
     col_idx = np.nonzero(eff.reshape(H * nbq, nbk))[1]
     ids = np.flatnonzero(live.reshape(-1))
     hh, rr = ids // nbq, ids % nbq
+    group_ptr = None
     if order == 0:
         perm = np.arange(ids.size)
     elif order == 1:
         perm = np.lexsort((rr, hh, -counts[ids]))
-    else:
+    elif order == 2:
         perm = np.lexsort((rr, -counts[ids], hh))
+    else:
+        # deal heads (heaviest first) to the lightest of 8 groups, with a heap
+        import heapq
+
+        weight = np.array([counts[h * nbq : (h + 1) * nbq].sum() for h in range(H)])
+        heap = [(0, g) for g in range(8)]
+        group_of = np.zeros(H, np.int64)
+        rank_in_group = np.zeros(H, np.int64)
+        size = [0] * 8
+        for h in np.lexsort((np.arange(H), -weight)):
+            load, g = heapq.heappop(heap)
+            group_of[h], rank_in_group[h] = g, size[g]
+            size[g] += 1
+            heapq.heappush(heap, (load + int(weight[h]), g))
+        c_live = counts[ids]
+        long_ = 2 * c_live * ids.size > 3 * c_live.sum()
+        # one lexsort: group, long rows before the others, then (count desc for long rows), head rank, r
+        perm = np.lexsort((rr, rank_in_group[hh], np.where(long_, -c_live, 0), ~long_, group_of[hh]))
+        group_ptr = np.concatenate([[0], np.cumsum(np.bincount(group_of[hh], minlength=8))])
     work = ids[perm]
     fan = [np.flatnonzero(rep[w // nbq] == w % nbq) for w in work]
     fan_ptr = np.concatenate([[0], np.cumsum([len(f) for f in fan])])
     fan_dst = np.concatenate(fan) if fan else np.zeros(0, np.int64)
-    return dict(row_ptr=row_ptr, col_idx=col_idx, repeat_src=rep.reshape(-1), work=work, fan_ptr=fan_ptr, fan_dst=fan_dst)
+    out = dict(row_ptr=row_ptr, col_idx=col_idx, repeat_src=rep.reshape(-1), work=work, fan_ptr=fan_ptr, fan_dst=fan_dst)
+    if group_ptr is not None:
+        out["group_ptr"] = group_ptr
+    return out
 
 
 def check_invariants(p, mask, repeat, H, N, bq, bk, order):
@@ -88,6 +111,31 @@ def check_invariants(p, mask, repeat, H, N, bq, bk, order):
         assert (np.diff(cnt) <= 0).all()
     if order == 2:
         assert (np.diff(work // nbq) >= 0).all()
+    if order == 3:
+        gp = p["group_ptr"]
+        assert p["n_groups"] == 8 and gp[0] == 0 and gp[8] == p["n_work"] and (np.diff(gp) >= 0).all()
+        heads_of = [sorted(set((work[gp[g] : gp[g + 1]] // nbq).tolist())) for g in range(8)]
+        assert sorted(h for hs in heads_of for h in hs) == sorted(set((work // nbq).tolist()))  # a head lives in one group
+        for g in range(8):
+            seg = work[gp[g] : gp[g + 1]]
+            hs = seg // nbq
+            # long rows lead, longest first; after them a head's rows are contiguous and ascending
+            c_seg = cnt[gp[g] : gp[g + 1]]
+            is_long = 2 * c_seg * p["n_work"] > 3 * p["nnz"]
+            n_long = int(is_long.sum())
+            assert is_long[:n_long].all() and (np.diff(c_seg[:n_long]) <= 0).all()
+            for h in set(hs[n_long:].tolist()):
+                idx = np.flatnonzero(hs[n_long:] == h)
+                assert (np.diff(idx) == 1).all() and (np.diff(seg[n_long:][idx]) > 0).all()
+        # greedy dealing keeps the groups within one head's weight of each other
+        w = np.array([cnt[gp[g] : gp[g + 1]].sum() for g in range(8)])
+        per_head = {}
+        for x, c in zip(work, cnt):
+            per_head[x // nbq] = per_head.get(x // nbq, 0) + c
+        if len(per_head) >= 8:
+            assert w.max() - w.min() <= max(per_head.values())
+    else:
+        assert p["n_groups"] == 1 and p["group_ptr"][0] == 0 and p["group_ptr"][1] == p["n_work"]
 
 
 def test_oracle_worked_example():
@@ -104,7 +152,7 @@ def test_oracle_vs_independent_construction(seed):
     dens = float(rng.choice([0.0, 0.1, 0.5, 0.9, 1.0]))
     mask, repeat = random_mask(seed, H, nbq, nbk, dens, float(rng.choice([0, 0.2, 0.6])), tail_partial=(N % bq) != 0)
     mask = mask * rng.integers(1, 255, size=mask.shape).astype(np.uint8)  # any non-zero byte = kept
-    for order in (0, 1, 2):
+    for order in (0, 1, 2, 3):
         p = compile_pattern(mask, repeat, H, N, bq, bk, order)
         q = independent_numpy_compile(mask, repeat, H, N, bq, bk, order)
         for name in q:
