@@ -105,6 +105,22 @@ def cpu_oracle_baseline(wl, n_blocks):
     }
 
 
+def profiled_traffic(args):
+    """HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this
+    exact command line (default workload and schedule); None for anything else."""
+    if args.workload != "wan480" or args.density is not None or args.repeat_frac is not None \
+            or args.heads is not None or args.order != 3 or args.no_persistent:
+        return None
+    path = os.path.join(ROOT, "profiles", "sparse_attn_fwd_wan480.txt")
+    try:
+        for line in open(path):
+            if line.startswith("roofline.traffic"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -186,7 +202,7 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS,
-            "traffic": None,
+            "traffic": profiled_traffic(args),
         },
     }
     if not args.no_cpu:
