@@ -1,0 +1,145 @@
+// Device-side building blocks shared by the attention kernels of this library:
+// vector types, LDS swizzles, the direct-to-LDS tile loader, bf16 packing and
+// the lane^32 exchange.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "calibatt.h"
+
+namespace calibatt_dev {
+
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+#define LDS_PTR(T) __attribute__((address_space(3))) T *
+
+struct FwdDims {
+  int B, H, N, nbq, nbk, n_work;
+  float scale_log2e;
+  int n_groups;                         // segments of the work list (1, or one per XCD)
+  int group_ptr[CALIBATT_GROUPS + 1];   // segment g = work[group_ptr[g] .. group_ptr[g+1])
+};
+
+template <int N_OUTSTANDING>
+__device__ __forceinline__ void wait_vmem() {
+  // waits until at most N_OUTSTANDING vector-memory operations of this wave are in flight
+  static_assert(N_OUTSTANDING == 0 || N_OUTSTANDING == 2 || N_OUTSTANDING == 4 || N_OUTSTANDING == 8 ||
+                N_OUTSTANDING == 16, "add the immediate below");
+  if constexpr (N_OUTSTANDING == 0) asm volatile("s_waitcnt vmcnt(0)");
+  else if constexpr (N_OUTSTANDING == 2) asm volatile("s_waitcnt vmcnt(2)");
+  else if constexpr (N_OUTSTANDING == 4) asm volatile("s_waitcnt vmcnt(4)");
+  else if constexpr (N_OUTSTANDING == 8) asm volatile("s_waitcnt vmcnt(8)");
+  else asm volatile("s_waitcnt vmcnt(16)");
+}
+
+// 16-byte-chunk XOR swizzles of the LDS tiles.  CH = chunks per row (D/8); one
+// 256-byte LDS line (all 64 banks) holds 16/CH rows.
+//  K: 16 lanes reading 16 consecutive rows at one chunk column hit 16 distinct chunks.
+//  V: a transposing read touches 4 consecutive rows x 4 consecutive chunks; they
+//     land on 16 distinct chunks.
+template <int D>
+__device__ __forceinline__ int k_swz(int row) {
+  constexpr int CH = D / 8;
+  return (row / (16 / CH)) % CH;
+}
+template <int D>
+__device__ __forceinline__ int v_swz(int row) {
+  constexpr int CH = D / 8;
+  return 4 * ((row / (16 / CH)) % (CH / 4));
+}
+
+// Raw buffer descriptor (V#) over one head's [N][D] bf16 matrix: loads past the
+// end return zero instead of faulting, which is how ragged tails are handled.
+__device__ __forceinline__ u32x4 head_rsrc(const uint16_t *base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  u32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  r[1] = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);  // stride 0, no swizzle
+  r[2] = bytes;
+  r[3] = 0x00020000u;
+  return r;
+}
+
+// One direct-to-LDS load: every lane fetches 16 bytes at rsrc.base + voff + soff
+// and the wave's 1 KB lands at LDS byte address lds_off + 16 * lane.  Issued as
+// inline asm so that the compiler keeps no record of LDS being written by an
+// in-flight vector-memory operation (it would otherwise drain vmcnt before
+// every LDS read); completion is tracked by hand with wait_vmem<>().
+__device__ __forceinline__ void dma_16B_per_lane(const u32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_off) {
+#ifdef CALIBATT_DEBUG_BUILTIN_DMA
+  __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)rsrc[1] << 32) | rsrc[0]), 0, rsrc[2], 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rr, (LDS_PTR(void))(uintptr_t)lds_off, 16, voff, soff, 0, 0);
+  return;
+#endif
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"  // one wait state between the M0 write and the LDS-DMA that reads it
+      "buffer_load_dwordx4 %1, %2, %3 offen lds"
+      :
+      : "s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff)
+      : "m0");
+}
+
+// Stream one ROWS x D bf16 tile global -> LDS.  Each instruction fills 1 KB of
+// LDS; LDS chunk (row, c') receives global chunk (row, c' ^ swz(row)).
+template <int D, int ROWS, int NT, bool FOR_V>
+struct TileLoader {
+  static constexpr int CH = D / 8;
+  static constexpr int RPI = NT / CH;            // rows filled per instruction slab
+  static constexpr int ITERS = ROWS / RPI;
+  static constexpr bool INVARIANT = (RPI % 16) == 0;  // swizzle repeats every 16 rows
+  static_assert(ROWS % RPI == 0, "tile must split evenly over the workgroup");
+
+  static __device__ __forceinline__ uint32_t lane_offset(int tid, int it) {
+    const int row = it * RPI + tid / CH;
+    const int cs = tid % CH;
+    const int c = cs ^ (FOR_V ? v_swz<D>(row) : k_swz<D>(row));
+    return (tid / CH) * (D * 2) + c * 16;
+  }
+
+  // lds_wave_off: LDS byte address of the tile + 1024 * wave index (wave-uniform)
+  static __device__ __forceinline__ void issue(const u32x4 rsrc, int row0, uint32_t lds_wave_off, int tid,
+                                               uint32_t lane_off0) {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const uint32_t voff = INVARIANT ? lane_off0 : lane_offset(tid, it);
+      const uint32_t soff = (uint32_t)(row0 + it * RPI) * (D * 2);
+      dma_16B_per_lane(rsrc, voff, soff, lds_wave_off + it * NT * 16);
+    }
+  }
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  bf16x2 t;
+  t[0] = (__bf16)lo;
+  t[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, t);
+}
+
+// After the swap, a holds {x[0..31], x[0..31]} and b holds {x[32..63], x[32..63]}:
+// every lane sees its own value and the one of lane ^ 32.  (Inline asm: the
+// two-result builtin folds both results into one when fed the same operand
+// twice.)  The leading s_nop covers the VALU-write -> permlane-read hazard.
+__device__ __forceinline__ void halves_of(float x, float &a, float &b) {
+  a = x;
+  b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float max_with_other_half(float x) {
+  float a, b;
+  halves_of(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+  float a, b;
+  halves_of(x, a, b);
+  return a + b;
+}
+
+
+}  // namespace calibatt_dev

@@ -1,0 +1,378 @@
+// Block-sparse attention forward for gfx950 (MI355X), bf16 in / fp32 accumulate.
+//
+// What it computes (paper, Section 2 Eq. 1-4 restricted by the block mask of
+// Section 3.2, run as in Section 3.4): for every computed query block r of a
+// head, loop over the kept key/value blocks listed in the CSR pattern, form
+// S = scale * Q_r K_c^T, fold it into a running row max / row sum (online
+// softmax), accumulate O += P V_c, and finally write O / rowsum.  Skipped
+// blocks are never loaded.  Query blocks marked as repeats (Section 3.3 at
+// block granularity) are not computed: the workgroup that owns their source
+// block writes its result to the source and to every block that copies it.
+//
+// Mapping to CDNA4:
+//  * one workgroup per (work item, batch index); BQ/32 wavefronts, each owning
+//    32 query rows;
+//  * both contractions use v_mfma_f32_32x32x16_bf16 in the "transposed" form
+//    S^T = K Q^T and O^T = V^T P^T, so that a lane owns ONE query column: the
+//    row max / row sum are in-lane reductions plus one exchange with lane^32,
+//    the rescale factor is a per-lane scalar, and the fp32 S^T accumulators
+//    are, after conversion to bf16, exactly the B operand of the second MFMA
+//    (no trip through LDS for P);
+//  * K and V tiles go global -> LDS with global_load_lds_dwordx4 (no staging
+//    registers).  K is read back with ds_read_b128 as the A operand; V stays
+//    row-major and is read with the transposing ds_read_b64_tr_b16;
+//  * both tiles are XOR-swizzled at 16-byte granularity (applied on the global
+//    side of the direct load) so the MFMA operand reads are bank-conflict free;
+//  * K and V have one LDS buffer each: K[i+1] streams in during softmax + PV of
+//    tile i, V[i+1] during QK^T + softmax of tile i+1; two workgroups per CU
+//    (64 KB LDS each at 128x128x128) let one workgroup's MFMAs overlap the
+//    other's softmax VALU work;
+//  * the epilogue stages the normalised bf16 tile in LDS and stores whole rows
+//    with 16-byte accesses to the block itself and to all its repeat targets.
+#pragma once
+#include "attn_common.h"
+
+namespace calibatt_dev {
+
+template <int D, int BQ, int BK>
+__global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_kernel(
+    const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
+    uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
+    int32_t *counter, const FwdDims p) {
+  constexpr int NW = BQ / 32;     // wavefronts per workgroup
+  constexpr int NT = NW * 64;     // threads
+  constexpr int CH = D / 8;       // 16-byte chunks per row
+  constexpr int KB = BK / 32;     // 32-key sub-blocks per tile
+  constexpr int DS = D / 16;      // k-slabs of the QK^T contraction
+  constexpr int DB = D / 32;      // 32-wide d blocks of O^T
+  constexpr int ROWB = D * 2;     // bytes per LDS row
+  constexpr int TILE_BYTES = BK * ROWB;
+  constexpr int OST = ROWB + 16;  // padded row stride of the output staging tile
+  constexpr int LDS_BYTES = (2 * TILE_BYTES > BQ * OST) ? 2 * TILE_BYTES : BQ * OST;
+  using LoadK = TileLoader<D, BK, NT, false>;
+  using LoadV = TileLoader<D, BK, NT, true>;
+  constexpr int LOADS_PER_WAVE = LoadK::ITERS;  // direct-to-LDS instructions per wave and tile
+
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // LDS_BYTES + 64 (work-item mailbox)
+  char *const ldsK = lds;
+  char *const ldsV = lds + TILE_BYTES;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int l32 = lane & 31;
+  const int g = lane >> 5;
+
+  const uint32_t k_lane_off = LoadK::lane_offset(tid, 0);
+  const uint32_t v_lane_off = LoadV::lane_offset(tid, 0);
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
+  const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t ldsK_wave = lds_base + wave_u * 1024;
+  const uint32_t ldsV_wave = ldsK_wave + TILE_BYTES;
+  const int N = p.N;
+  const int n_items = p.n_work * p.B;
+  volatile int *const mailbox = reinterpret_cast<volatile int *>(lds + LDS_BYTES);
+
+  // Persistent workgroups (counter != nullptr): every workgroup pops (work item,
+  // batch index) pairs from per-group counters until all groups are drained, so
+  // uneven rows balance dynamically.  With one group per XCD a workgroup starts
+  // on the group of the XCD it runs on (the heads of a group then share that
+  // XCD's L2) and moves on to the next group, for good, once one is empty.
+  // Otherwise: one workgroup per pair.
+#ifdef CALIBATT_DEBUG_TIMING
+  const long long dbg_t0 = wall_clock64();
+  int dbg_items = 0, dbg_tiles = 0;
+#endif
+  int cur_group = 0, groups_left = p.n_groups;
+  if (counter && p.n_groups > 1)
+    cur_group = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) % p.n_groups;  // HW_REG_XCC_ID[3:0]
+  for (int wg_item = blockIdx.x;;) {
+  if (counter) {
+    if (tid == 0) {
+      int found = -1;
+      while (groups_left > 0) {
+        const int it = atomicAdd(counter + cur_group, 1);
+        if (it < (p.group_ptr[cur_group + 1] - p.group_ptr[cur_group]) * p.B) {
+          found = p.group_ptr[cur_group] * p.B + it;
+          break;
+        }
+        cur_group = cur_group + 1 == p.n_groups ? 0 : cur_group + 1;
+        --groups_left;
+      }
+      *mailbox = found;
+    }
+    __syncthreads();
+    wg_item = __builtin_amdgcn_readfirstlane(*mailbox);
+    if (wg_item < 0) break;
+  }
+  if (wg_item >= n_items) break;
+  const int item = wg_item / p.B;
+  const int b = wg_item - item * p.B;
+  const int id = work[item];
+#ifdef CALIBATT_DEBUG_TIMING
+  ++dbg_items;
+  dbg_tiles += row_ptr[id + 1] - row_ptr[id];
+#endif
+  const int h = id / p.nbq;
+  const int r = id - h * p.nbq;
+  const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
+  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
+  const u32x4 Vres = head_rsrc(gv + head_off, (uint32_t)N * ROWB);
+
+  const int cbeg = row_ptr[id];
+  const int cend = row_ptr[id + 1];
+
+  // The row's kv-block list is held 64 entries at a time in one VGPR (lane j =
+  // entry j) and read back with v_readlane: no memory operation per tile.
+  const int n_tiles = cend - cbeg;
+  int col_cache = n_tiles > 0 ? col_idx[cbeg + min(lane, n_tiles - 1)] : 0;
+  // first K and V tiles
+  int c_next = 0;
+  if (n_tiles > 0) {
+    c_next = __builtin_amdgcn_readlane(col_cache, 0);
+    LoadK::issue(Kres, c_next * BK, ldsK_wave, tid, k_lane_off);
+    LoadV::issue(Vres, c_next * BK, ldsV_wave, tid, v_lane_off);
+  }
+  // Q^T as MFMA B operand: lane (query l32, half g) holds d = 16 s + 8 g + [0,8)
+  bf16x8 qreg[DS];
+  {
+    int qrow = r * BQ + wave * 32 + l32;
+    qrow = qrow < N ? qrow : N - 1;
+    const uint16_t *qp = gq + head_off + (size_t)qrow * D + 8 * g;
+#pragma unroll
+    for (int s = 0; s < DS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+    // touch the registers here so that the compiler's wait for these loads sits
+    // in front of the loop and not inside it
+#pragma unroll
+    for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qreg[s]));
+  }
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+  float m_run = -INFINITY;  // running max of scaled (log2-domain) logits, shared by lane and lane^32
+  float l_run = 0.f;        // this lane's share of the running row sum
+
+  // K operand row for MFMA row i = l32: swap bits 2 and 3 so that the 8 S^T
+  // values a lane holds per 16-key slab belong to 8 consecutive keys.  With the
+  // XOR swizzle the address of k-slab s is k_addr0 ^ (s << 5).
+  const int krow_in_kb = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+  const uint32_t k_addr0 = krow_in_kb * ROWB + ((g ^ k_swz<D>(krow_in_kb)) << 4);
+  // transposing V read: 16-lane block -> (d sub-block, key half); lane L16 in block
+  const int L16 = lane & 15;
+  const int blk = lane >> 4;
+  const int v_row_off = 8 * (blk >> 1) + (L16 >> 2);  // + 32 kb + 16 s2 + 4 t
+  uint32_t v_addr[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    v_addr[db] = v_row_off * ROWB + (((4 * db + 2 * (blk & 1) + ((L16 & 3) >> 1)) ^ v_swz<D>(v_row_off)) << 4) +
+                 (L16 & 1) * 8;
+
+  const float sc = p.scale_log2e;
+
+  for (int ti = 0; ti < n_tiles; ++ti) {
+    const int c = c_next;
+    const bool has_next = ti + 1 < n_tiles;
+    if (has_next) {
+      if (((ti + 1) & 63) == 0) col_cache = col_idx[cbeg + min(ti + 1 + lane, n_tiles - 1)];
+      c_next = __builtin_amdgcn_readlane(col_cache, (ti + 1) & 63);
+    }
+
+    // ---- S^T = K Q^T --------------------------------------------------------
+    // K[ci] was issued before V[ci]: V's loads may stay in flight.
+    wait_vmem<LOADS_PER_WAVE>();
+    __syncthreads();
+    f32x16 s_acc[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.f;
+    // k-slab outer, key sub-block inner: consecutive MFMAs hit different
+    // accumulators; the A operands of slab s+1 are read while slab s multiplies.
+    {
+      bf16x8 ka[2][KB];
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+        ka[0][kb] = *reinterpret_cast<const bf16x8 *>(ldsK + (k_addr0 + kb * 32 * ROWB));
+#pragma unroll
+      for (int s = 0; s < DS; ++s) {
+        if (s + 1 < DS) {
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+            ka[(s + 1) & 1][kb] =
+                *reinterpret_cast<const bf16x8 *>(ldsK + ((k_addr0 ^ ((s + 1) << 5)) + kb * 32 * ROWB));
+        }
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+          s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][kb], qreg[s], s_acc[kb], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab 0
+#pragma unroll
+      for (int s = 0; s < DS; ++s) {
+        if (s + 1 < DS) __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab s+1
+        __builtin_amdgcn_sched_group_barrier(0x008, KB, 0);                  // MFMAs of slab s
+      }
+    }
+    __syncthreads();  // every wave is done with the K tile
+    if (has_next) LoadK::issue(Kres, c_next * BK, ldsK_wave, tid, k_lane_off);
+
+    // ---- online softmax (log2 domain) ----------------------------------------
+    float sc_t = sc;  // multiplier still to be applied to s_acc
+    if (c == p.nbk - 1 && (N % BK) != 0) {
+      // ragged last block: scale now, put keys >= N at -inf, continue with multiplier 1
+      const int key0 = c * BK + 8 * g;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
+          s_acc[kb][v] = key < N ? s_acc[kb][v] * sc : -INFINITY;
+        }
+      sc_t = 1.0f;
+    }
+    float m_loc;
+    if (sc_t >= 0.f) {
+      m_loc = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m_loc = fmaxf(m_loc, s_acc[kb][v]);
+    } else {
+      m_loc = INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m_loc = fminf(m_loc, s_acc[kb][v]);
+    }
+    m_loc = max_with_other_half(m_loc * sc_t);
+    const float m_new = fmaxf(m_run, m_loc);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
+    m_run = m_new;
+    // P = exp2(sc * S - m) rounded to bf16 pairs; the row sum is taken over the
+    // rounded values (two per v_dot2c with a vector of ones), so numerator and
+    // denominator of the final division see the same probabilities.
+    float psum = 0.f;
+    uint32_t pb[KB][8];  // bf16 pairs: pb[kb][4*s2 + j] = keys (2j, 2j+1) of 16-key slab s2
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; v += 2) {
+#ifdef CALIBATT_DEBUG_NO_EXP
+        const float p0 = s_acc[kb][v], p1 = s_acc[kb][v + 1];
+#else
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v], sc_t, -m_new));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v + 1], sc_t, -m_new));
+#endif
+        const uint32_t pk = pack_bf16(p0, p1);
+        pb[kb][v >> 1] = pk;
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, psum, false);
+      }
+    l_run = l_run * alpha + psum;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+    }
+
+    // ---- O^T += V^T P^T -----------------------------------------------------
+    if (has_next) wait_vmem<LOADS_PER_WAVE>(); else wait_vmem<0>();
+    __syncthreads();
+    {
+      // 16-key slab j = 2 kb + s2: V^T operands of slab j+1 are read while slab j multiplies
+      u32x4 va[2][DB];
+      auto v_read = [&](int j, int st) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const char *a = ldsV + v_addr[db] + 16 * j * ROWB;
+          const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(a)));
+          const u32x2 hi =
+              __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(a + 4 * ROWB)));
+          va[st][db] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+        }
+      };
+      v_read(0, 0);
+#pragma unroll
+      for (int j = 0; j < 2 * KB; ++j) {
+        if (j + 1 < 2 * KB) v_read(j + 1, (j + 1) & 1);
+        const int kb = j >> 1, s2 = j & 1;
+        const u32x4 pw = {pb[kb][4 * s2 + 0], pb[kb][4 * s2 + 1], pb[kb][4 * s2 + 2], pb[kb][4 * s2 + 3]};
+        const bf16x8 pB = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[j & 1][db]), pB, o[db], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
+#pragma unroll
+      for (int j = 0; j < 2 * KB; ++j) {
+        if (j + 1 < 2 * KB) __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
+      }
+    }
+    __syncthreads();  // every wave is done with the V tile
+    if (has_next) LoadV::issue(Vres, c_next * BK, ldsV_wave, tid, v_lane_off);
+  }
+
+  // ---- normalise, stage in LDS, store to the block and its repeat targets ----
+  const float l_tot = sum_with_other_half(l_run);
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  __syncthreads();
+  {
+    char *orow = lds + (wave * 32 + l32) * OST;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        u32x2 w;
+        w[0] = pack_bf16(o[db][4 * a + 0] * inv, o[db][4 * a + 1] * inv);
+        w[1] = pack_bf16(o[db][4 * a + 2] * inv, o[db][4 * a + 3] * inv);
+        *reinterpret_cast<u32x2 *>(orow + (32 * db + 8 * a + 4 * g) * 2) = w;
+      }
+  }
+  __syncthreads();
+  const int fbeg = fan_ptr[item];
+  const int fend = fan_ptr[item + 1];
+  uint16_t *const out_head = gout + head_off;
+  for (int f = fbeg - 1; f < fend; ++f) {
+    const int rd = f < fbeg ? r : fan_dst[f];
+    const int rows_valid = min(BQ, N - rd * BQ);
+    uint16_t *dst = out_head + (size_t)rd * BQ * D;
+#pragma unroll 4
+    for (int L = tid; L < BQ * CH; L += NT) {
+      const int row = L / CH;
+      const int cc = L % CH;
+      if (row < rows_valid) {
+        const u32x4 val = *reinterpret_cast<const u32x4 *>(lds + row * OST + cc * 16);
+        *reinterpret_cast<u32x4 *>(dst + (size_t)row * D + cc * 8) = val;
+      }
+    }
+  }
+  if (!counter) break;
+  __syncthreads();  // staging tile fully read before the next item's loads overwrite it
+  }  // work-item loop
+
+#ifdef CALIBATT_DEBUG_TIMING
+  if (counter && tid == 0) {
+    long long *dbg = reinterpret_cast<long long *>(counter + 32) + 4 * blockIdx.x;
+    dbg[0] = dbg_t0;
+    dbg[1] = wall_clock64();
+    dbg[2] = dbg_items;
+    dbg[3] = dbg_tiles | ((long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) << 32);
+  }
+#endif
+  // Last workgroup out re-arms the counter pair for the next launch.
+  if (counter && tid == 0) {
+    __threadfence();
+    if (atomicAdd(counter + CALIBATT_GROUPS, 1) == (int)gridDim.x - 1) {
+      for (int i = 0; i <= CALIBATT_GROUPS; ++i) counter[i] = 0;
+      __threadfence();
+    }
+  }
+}
+
+
+}  // namespace calibatt_dev
