@@ -3,7 +3,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstdlib>
+#include <cstring>
+
 #include "attn_kernel_2wg.h"
+#include "attn_kernel_pipe.h"
 #include "calibatt.h"
 
 namespace {
@@ -51,12 +55,31 @@ int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, c
   return hipGetLastError() == hipSuccess ? CALIBATT_OK : CALIBATT_ERR_LAUNCH;
 }
 
+// CALIBATT_KERNEL=pipe in the environment selects the in-wave pipelined kernel
+// where its shape is covered, CALIBATT_KERNEL=2wg the two-workgroups-per-CU one.
+bool pipelined_wanted() {
+  static const bool wanted = [] {
+    const char *e = std::getenv("CALIBATT_KERNEL");
+    return e && std::strcmp(e, "pipe") == 0;
+  }();
+  return wanted;
+}
+
 template <int D, int BQ, int BK>
-int launch(const FwdPtrs &a, const FwdDims &p, hipStream_t stream) {
+int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) {
   const long long items = (long long)p.n_work * p.B;
   if (items <= 0) return CALIBATT_OK;
   if (items > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
   int slots = 0;
+  if constexpr (D == 128 && BQ == 128 && BK == 128) {
+    if (max_row <= PIPE_COL_CAP && pipelined_wanted()) {
+      static DevInfo info[64];
+      constexpr int SMEM = PipeLds<D, BQ, BK>::BYTES;
+      auto kernel = sparse_attn_fwd_pipe_kernel<D, BQ, BK>;
+      if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
+      return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
+    }
+  }
   constexpr int TILE_BYTES = BK * D * 2;
   constexpr int OST = D * 2 + 16;
   constexpr int LDS_BYTES = (2 * TILE_BYTES > BQ * OST) ? 2 * TILE_BYTES : BQ * OST;
@@ -115,7 +138,7 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
   for (int g = 0; g <= CALIBATT_GROUPS; ++g) p.group_ptr[g] = pattern->group_ptr[g];
   hipStream_t s = (hipStream_t)stream;
 #define CALIBATT_CASE(d, bq, bk) \
-  if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, s);
+  if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, pattern->max_row, s);
   CALIBATT_CASE(128, 128, 128)
   CALIBATT_CASE(128, 128, 64)
   CALIBATT_CASE(128, 64, 128)
