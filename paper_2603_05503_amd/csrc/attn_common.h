@@ -92,7 +92,8 @@ struct TileLoader {
   static constexpr int CH = D / 8;
   static constexpr int RPI = NT / CH;            // rows filled per instruction slab
   static constexpr int ITERS = ROWS / RPI;
-  static constexpr bool INVARIANT = (RPI % 16) == 0;  // swizzle repeats every 16 rows
+  // lane offsets are the same for every instruction when the swizzle period (16 rows for K, 4 for V) divides RPI
+  static constexpr bool INVARIANT = (RPI % (FOR_V ? 4 : 16)) == 0;
   static_assert(ROWS % RPI == 0, "tile must split evenly over the workgroup");
 
   static __device__ __forceinline__ uint32_t lane_offset(int tid, int it) {

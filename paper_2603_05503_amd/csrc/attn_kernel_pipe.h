@@ -1,39 +1,46 @@
 // Block-sparse attention forward for gfx950, software-pipelined variant for
-// 128-row query blocks, 128-row kv blocks and head dimension 128: one workgroup
-// per CU, one wavefront per SIMD, and the softmax of one kv tile overlapped,
-// inside every wavefront, with the matrix products of its neighbours.
+// 128-row query blocks, 128-row kv blocks and head dimension 128.
 //
 // What it computes is the same as the two-workgroup kernel (paper, Section 2
 // Eq. 1-4 restricted to the kept blocks of Section 3.2, run as in Section 3.4;
 // repeated query blocks of Section 3.3 written by the owner of their source).
 //
-// Schedule of one query block with kept tiles 0..n-1 (S_t = K_t Q^T, P_t =
-// exp2(sc S_t - m), O += V_t^T P_t):
+// Shape of the work: a workgroup of TWO wavefronts owns one query block, each
+// wavefront 64 queries (two groups of 32), two workgroups per CU so that every
+// SIMD hosts one wavefront with the whole register file.  An MFMA operand read
+// from LDS then feeds two MFMAs (one per query group): with 32 queries per
+// wavefront the LDS reads of the four wavefronts take as long as the MFMAs
+// themselves and cannot be hidden.  Every kept 128-key block is processed as
+// two sub-tiles of 64 keys.
 //
-//   phase A(i) : MFMA  S_{i+1} = K_{i+1} Q^T         | VALU  later part of P_i   | DMA V_{i+1}
-//   phase B1(i): MFMA  O += V_i^T P_i, slabs 0-1     | VALU  row maximum of S_{i+1}
-//   phase B2(i): MFMA  O += V_i^T P_i, slabs 2-7     | VALU  first part of P_{i+1} | DMA K_{i+3}
+// Schedule of one query block with sub-tiles 0..T-1 (S_t = K_t Q^T, P_t =
+// exp2(sc S_t - m), O += V_t^T P_t), inside every wavefront:
+//
+//   phase A(i) : MFMA  S_{i+1} = K_{i+1} Q^T         | VALU  later part of P_i     | DMA V_{i+1}
+//   phase B1(i): MFMA  O += V_i^T P_i, first slab    | VALU  row maxima of S_{i+1}
+//   phase B2(i): MFMA  O += V_i^T P_i, other slabs   | VALU  first part of P_{i+1} | DMA K_{i+3}
 //
 // The compiler neither interleaves MFMA and VALU streams by itself nor keeps
-// 250 live vector registers where they are, so S, P, O, Q and the MFMA
-// operands live in registers the compiler never allocates (the kernel is built
-// with a cap of 64 vector registers; v64-v255 and a64-a223 are addressed by
-// name), and every instruction touching them comes from attn_pipe_asm.h, which
-// a script in this directory writes.  What is left to the compiler is the
-// control flow, addresses, and the per-row scalars m, l, alpha.
+// 400 live registers where they are, so S, P, O, Q and the MFMA operands live
+// in registers the compiler never allocates (the kernel is built with a cap of
+// 64 vector registers; v64-v255 and a16-a255 are addressed by name; the build
+// verifies that the compiler stayed out of them), and every instruction
+// touching them comes from attn_pipe_asm.h, which a script in this directory
+// writes.  What is left to the compiler is the control flow, addresses, and
+// the per-row scalars m, l, alpha.
 //
-// The reference maximum m only moves when a tile's row maximum exceeds it by
-// more than 8 in the log2 domain (probabilities then stay below 2^8: no
+// The reference maximum m only moves when a sub-tile's row maximum exceeds it
+// by more than 8 in the log2 domain (probabilities then stay below 2^8: no
 // overflow, same relative precision in bf16), so the rescale of O and of the
-// row sum is a rare, wave-uniform branch instead of 64 multiplies per tile; O
-// is rescaled after the product that was still formed with the old reference.
-// A negative softmax scale is folded into the sign of Q, so only maxima are
-// ever needed.
+// row sum is a rare, wave-uniform branch instead of 128 multiplies per
+// sub-tile; O is rescaled after the product that was still formed with the old
+// reference.  A negative softmax scale is folded into the sign of Q, so only
+// maxima are ever needed.
 //
-// K and V tiles are double-buffered in LDS (4 x 32 KB) and arrive by
+// K and V sub-tiles are double-buffered in LDS (4 x 16 KB) and arrive by
 // buffer_load ... lds issued from inside the phases, three phases ahead of
-// their first use; there are two barriers per tile.  The kv-block list of the
-// row is copied to LDS once per query block.
+// their first use; there are two barriers (of two wavefronts) per sub-tile.
+// The kv-block list of the row is copied to LDS once per query block.
 #pragma once
 #include <type_traits>
 
@@ -42,39 +49,46 @@
 
 namespace calibatt_dev {
 
-constexpr int PIPE_COL_CAP = 4096;  // kv-block list entries held in LDS per query block
+constexpr int PIPE_COL_CAP = 2048;  // kv-block list entries held in LDS per query block
+constexpr int PIPE_THREADS = 128;   // two wavefronts of 64 queries
 
 template <int D, int BQ, int BK>
 struct PipeLds {
-  static constexpr int TILE = BK * D * 2;
+  static constexpr int SUB = BK / 2;           // keys per sub-tile
+  static constexpr int TILE = SUB * D * 2;     // bytes of one K or V sub-tile
   static constexpr int MAILBOX = 4 * TILE;
   static constexpr int COLS = MAILBOX + 64;
   static constexpr int BYTES = COLS + PIPE_COL_CAP * 4;
 };
 
-__device__ __forceinline__ void pipe_barrier() { asm volatile("s_barrier"); }
+__device__ __forceinline__ void pipe_barrier() {
+#ifndef PIPE_DEBUG_NO_BARRIER
+  asm volatile("s_barrier");
+#endif
+}
 
 template <int D, int BQ, int BK>
-__global__ __launch_bounds__(BQ * 2, 1) __attribute__((amdgpu_num_vgpr(64))) void sparse_attn_fwd_pipe_kernel(
+__global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64))) void sparse_attn_fwd_pipe_kernel(
     const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
     uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
     int32_t *counter, const FwdDims p) {
-  static_assert(D == 128 && BQ == 128 && BK == 128, "the instruction streams are written for 128 x 128 x 128 tiles");
-  constexpr int NT = 256;
+  static_assert(D == 128 && BQ == 128 && BK == 128, "the instruction streams are written for 128 x 128 x 128 blocks");
+  constexpr int NT = PIPE_THREADS;
   constexpr int CH = D / 8;
   constexpr int DS = 8;   // k-slabs of S = K Q^T
   constexpr int DB = 4;   // 32-wide d blocks of O^T
   constexpr int ROWB = D * 2;
-  constexpr int TILE = BK * ROWB;
-  constexpr int OST = ROWB + 16;
   using Lds = PipeLds<D, BQ, BK>;
-  using LoadK = TileLoader<D, BK, NT, false>;
-  using LoadV = TileLoader<D, BK, NT, true>;
-  constexpr int LPW = LoadK::ITERS;  // DMA instructions per wave and tile
-  static_assert(LPW == 8 && LoadK::INVARIANT && LoadV::INVARIANT, "shape not covered by this kernel");
-  static_assert(BQ * OST <= 2 * TILE, "output staging must fit into the K buffers");
-  static_assert(TILE == 32768, "LDS offsets in the instruction streams assume 32 KB tiles");
+  constexpr int SUB = Lds::SUB;
+  constexpr int TILE = Lds::TILE;
+  constexpr int OST = ROWB + 16;
+  using LoadK = TileLoader<D, SUB, NT, false>;
+  using LoadV = TileLoader<D, SUB, NT, true>;
+  constexpr int LPW = LoadK::ITERS;  // DMA instructions per wave and sub-tile
+  static_assert(LPW == 8 && LoadV::INVARIANT, "shape not covered by this kernel");
+  static_assert(BQ * OST <= 4 * TILE, "output staging must fit into the K and V buffers");
+  static_assert(TILE == 16384, "LDS offsets in the instruction streams assume 16 KB sub-tiles");
   constexpr float RESCALE_STEP = 8.0f;
 
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -84,7 +98,8 @@ __global__ __launch_bounds__(BQ * 2, 1) __attribute__((amdgpu_num_vgpr(64))) voi
   const int l32 = lane & 31;
   const int g = lane >> 5;
 
-  const uint32_t k_lane_off = LoadK::lane_offset(tid, 0);
+  // lane offsets of the direct-to-LDS loads; the K swizzle differs between even and odd instructions
+  const uint32_t k_lane_off0 = LoadK::lane_offset(tid, 0), k_lane_off1 = LoadK::lane_offset(tid, 1);
   const uint32_t v_lane_off = LoadV::lane_offset(tid, 0);
   const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
   const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -96,7 +111,7 @@ __global__ __launch_bounds__(BQ * 2, 1) __attribute__((amdgpu_num_vgpr(64))) voi
 
   // MFMA operand addresses (see the two-workgroup kernel for the derivation); the
   // XOR swizzle makes the K address of k-slab s equal to k_addr[0] ^ (s << 5).
-  // Buffer and sub-block offsets are immediates in the instruction streams.
+  // Buffer, sub-block and slab offsets are immediates in the instruction streams.
   const int krow_in_kb = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
   uint32_t k_addr[DS];
 #pragma unroll
@@ -110,11 +125,12 @@ __global__ __launch_bounds__(BQ * 2, 1) __attribute__((amdgpu_num_vgpr(64))) voi
   for (int db = 0; db < DB; ++db)
     v_addr[db] = lds_base + 2 * TILE + v_row_off * ROWB +
                  (((4 * db + 2 * (blk & 1) + ((L16 & 3) >> 1)) ^ v_swz<D>(v_row_off)) << 4) + (L16 & 1) * 8;
-  const uint32_t o_addr = lds_base + (wave * 32 + l32) * OST + 8 * g;  // output staging row of this lane
+  // output staging rows of this lane's two queries (query group qg: row 64 wave + 32 qg + l32)
+  const uint32_t o_addr0 = lds_base + (wave * 64 + l32) * OST + 8 * g;
+  const uint32_t o_addr1 = o_addr0 + 32 * OST;
   // softmax scale in the log2 domain; its sign moves into Q
-  const bool neg_scale = p.scale_log2e < 0.f;
   const float sc = fabsf(p.scale_log2e);
-  const uint32_t q_flip = neg_scale ? 0x80008000u : 0u;
+  const uint32_t q_flip = p.scale_log2e < 0.f ? 0x80008000u : 0u;
 
   int cur_group = 0, groups_left = p.n_groups;
   if (counter && p.n_groups > 1)
@@ -154,162 +170,170 @@ __global__ __launch_bounds__(BQ * 2, 1) __attribute__((amdgpu_num_vgpr(64))) voi
     // kv-block list of this row -> LDS (read back as wave-uniform values)
     for (int t = tid; t < n; t += NT) colbuf[t] = col_idx[cbeg + t];
     __syncthreads();
-    auto col = [&](int t) { return __builtin_amdgcn_readfirstlane(colbuf[t]); };
-    auto issue_k = [&](int t) { LoadK::issue(Kres, col(t) * BK, lds_wave + (t & 1) * TILE, tid, k_lane_off); };
-    auto issue_v = [&](int t) { LoadV::issue(Vres, col(t) * BK, lds_wave + (2 + (t & 1)) * TILE, tid, v_lane_off); };
+    // sub-tile t = half (t & 1) of kv block colbuf[t >> 1]; T of them (the second half of a ragged
+    // last block is dropped when it holds no key)
+    int T = 2 * n;
+    if (n > 0 && N - __builtin_amdgcn_readfirstlane(colbuf[n - 1]) * BK <= SUB) --T;
+    auto first_key = [&](int t) { return colbuf[t >> 1] * BK + (t & 1) * SUB; };  // wave-uniform, in a vector register
+    auto first_key_s = [&](int t) { return __builtin_amdgcn_readfirstlane(first_key(t)); };
+    auto issue_k = [&](int t) { LoadK::issue(Kres, first_key_s(t), lds_wave + (t & 1) * TILE, tid, k_lane_off0); };
+    auto issue_v = [&](int t) { LoadV::issue(Vres, first_key_s(t), lds_wave + (2 + (t & 1)) * TILE, tid, v_lane_off); };
 
-    if (n > 0) {
+    if (T > 0) {
       issue_k(0);
       issue_v(0);
-      if (n > 1) issue_k(1);
+      if (T > 1) issue_k(1);
     }
-    // Q^T as MFMA B operand: lane (query l32, half g) holds d = 16 s + 8 g + [0,8) of k-slab s
+    // Q^T as MFMA B operand: lane (query l32 of group qg, half g) holds d = 16 s + 8 g + [0,8) of k-slab s
     {
-      int qrow = r * BQ + wave * 32 + l32;
-      qrow = qrow < N ? qrow : N - 1;
-      const u32x4 *qp = reinterpret_cast<const u32x4 *>(gq + head_off + (size_t)qrow * D + 8 * g);
-      u32x4 qa[4], qb[4];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        qa[s] = qp[2 * s];
-        qb[s] = qp[2 * (s + 4)];
-      }
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        qa[s] ^= q_flip;
-        qb[s] ^= q_flip;
-      }
-      pipe_load_q<0>(qa[0], qa[1], qa[2], qa[3]);
-      pipe_load_q<1>(qb[0], qb[1], qb[2], qb[3]);
+      const int q0 = r * BQ + wave * 64 + l32;
+      const int qrow0 = q0 < N ? q0 : N - 1, qrow1 = q0 + 32 < N ? q0 + 32 : N - 1;
+      const u32x4 *qp0 = reinterpret_cast<const u32x4 *>(gq + head_off + (size_t)qrow0 * D + 8 * g);
+      const u32x4 *qp1 = reinterpret_cast<const u32x4 *>(gq + head_off + (size_t)qrow1 * D + 8 * g);
+      auto load_part = [&](auto part) {
+        constexpr int PART = decltype(part)::value;
+        u32x4 a0 = qp0[2 * (2 * PART)], a1 = qp1[2 * (2 * PART)];
+        u32x4 b0 = qp0[2 * (2 * PART + 1)], b1 = qp1[2 * (2 * PART + 1)];
+        a0 ^= q_flip; a1 ^= q_flip; b0 ^= q_flip; b1 ^= q_flip;
+        pipe_load_q<PART>(a0, a1, b0, b1);
+      };
+      load_part(std::integral_constant<int, 0>{});
+      load_part(std::integral_constant<int, 1>{});
+      load_part(std::integral_constant<int, 2>{});
+      load_part(std::integral_constant<int, 3>{});
     }
     pipe_zero_o();
 
-    float m_ref = -INFINITY;    // reference maximum (log2 domain), same in lane and lane^32
-    float l0 = 0.f, l1 = 0.f;   // this lane's share of the row sum (two partial sums), relative to m_ref
-    float alpha_o = 1.f;        // factor O still has to be multiplied with
-    float sc_t[2] = {sc, sc};   // multiplier of S of even / odd tiles (1 once a ragged tile was scaled and masked)
+    // per query group of this lane:
+    float m_ref[2] = {-INFINITY, -INFINITY};  // reference maximum (log2 domain), same in lane and lane^32
+    float l[2][2] = {{0.f, 0.f}, {0.f, 0.f}}; // this lane's share of the row sum (two partial sums), relative to m_ref
+    float alpha_o[2] = {1.f, 1.f};            // factor O still has to be multiplied with
+    float sc_t[2] = {sc, sc};  // multiplier of S of even / odd sub-tiles (1 once a ragged one was scaled and masked)
 
-    // ragged last kv block: scale and mask S of tile parity T now, continue with multiplier 1
-    auto mask_if_tail = [&](auto tpar, int c) {
-      constexpr int T = decltype(tpar)::value;
-      sc_t[T] = sc;
-      if (c == p.nbk - 1 && (N % BK) != 0) {
-        pipe_mask_tail<T>(sc, N - c * BK - 8 * g, -INFINITY);
-        sc_t[T] = 1.0f;
+    // ragged end of the key sequence: scale and mask S of sub-tile parity TP now, continue with multiplier 1
+    auto mask_if_tail = [&](auto tpar, int key0) {
+      constexpr int TP = decltype(tpar)::value;
+      sc_t[TP] = sc;
+      if (key0 + SUB > N) {
+        pipe_mask_tail<TP>(sc, N - key0 - 8 * g, -INFINITY);
+        sc_t[TP] = 1.0f;
       }
     };
-    // the (rare) move of the reference maximum, given this lane's maximum of the raw logits
-    auto new_tile_max = [&](float mx, float s_mul) {
-      const float m_loc = max_with_other_half(mx * s_mul);
-      const bool up = m_loc > m_ref + RESCALE_STEP;
-      if (__any(up)) {
-        const float a = up ? __builtin_amdgcn_exp2f(m_ref - m_loc) : 1.0f;  // 0 while m_ref is still -inf
-        l0 *= a;
-        l1 *= a;
-        alpha_o *= a;
-        m_ref = up ? m_loc : m_ref;
+    // the (rare) move of the reference maxima, given this lane's maxima of the raw logits
+    auto new_tile_max = [&](const float (&mx)[2], float s_mul) {
+      const float m0 = max_with_other_half(mx[0] * s_mul), m1 = max_with_other_half(mx[1] * s_mul);
+      const bool up0 = m0 > m_ref[0] + RESCALE_STEP, up1 = m1 > m_ref[1] + RESCALE_STEP;
+      if (__any(up0 || up1)) {
+        const float a0 = up0 ? __builtin_amdgcn_exp2f(m_ref[0] - m0) : 1.0f;  // 0 while m_ref is still -inf
+        const float a1 = up1 ? __builtin_amdgcn_exp2f(m_ref[1] - m1) : 1.0f;
+        l[0][0] *= a0;
+        l[0][1] *= a0;
+        l[1][0] *= a1;
+        l[1][1] *= a1;
+        alpha_o[0] *= a0;
+        alpha_o[1] *= a1;
+        m_ref[0] = up0 ? m0 : m_ref[0];
+        m_ref[1] = up1 ? m1 : m_ref[1];
       }
     };
-    auto wait_tiles = [&](int tiles_in_flight) {  // DMA of older tiles has landed
+    auto wait_tiles = [&](int tiles_in_flight) {  // DMA of older sub-tiles has landed
+#ifdef PIPE_DEBUG_NO_VMWAIT
+      return;
+#endif
       if (tiles_in_flight >= 2) wait_vmem<2 * LPW>();
       else if (tiles_in_flight == 1) wait_vmem<LPW>();
       else wait_vmem<0>();
     };
     auto rescale_o_if_pending = [&]() {
-      if (__any(alpha_o != 1.0f)) {
-        pipe_rescale_o(alpha_o);
-        alpha_o = 1.0f;
+      if (__any(alpha_o[0] != 1.0f || alpha_o[1] != 1.0f)) {
+        pipe_rescale_o<0>(alpha_o[0]);
+        pipe_rescale_o<1>(alpha_o[1]);
+        alpha_o[0] = alpha_o[1] = 1.0f;
       }
     };
 
-    // One tile step with a successor (i + 1 < n), PAR = i & 1: tile i uses the S / P registers and
-    // the V buffer of parity PAR, tile i+1 the other ones and K buffer 1 - PAR.
-    // c1 / c3 = kv block of tile i+1 / i+3.
-    auto stage_full = [&](auto par, int i, int c1, int c3) {
+    // One sub-tile step with a successor (i + 1 < T), PAR = i & 1: sub-tile i uses the S / P registers
+    // and the V buffer of parity PAR, sub-tile i+1 the other ones and K buffer 1 - PAR.
+    // k1 / k3 = first key of sub-tile i+1 / i+3.
+    auto stage_full = [&](auto par, int i, int k1, int k3) {
       constexpr int PAR = decltype(par)::value;
       using Y = std::integral_constant<int, 1 - PAR>;
       rescale_o_if_pending();
-      pipe_phase_a<PAR>(k_addr, sc_t[PAR], m_ref, l0, l1, Vres, v_lane_off, (uint32_t)c1 * (BK * ROWB),
+      pipe_phase_a<PAR>(k_addr, sc_t[PAR], m_ref, l, Vres, v_lane_off, v_lane_off, (uint32_t)k1 * ROWB,
                         lds_wave + (2 + (1 - PAR)) * TILE);
-      wait_tiles((i + 2 < n ? 1 : 0) + 1);  // V_i landed; K_{i+2}, V_{i+1} may be in flight
+      wait_tiles((i + 2 < T ? 1 : 0) + 1);  // V_i landed; K_{i+2}, V_{i+1} may be in flight
       pipe_barrier();
-      mask_if_tail(Y{}, c1);
-      float mx;
+      mask_if_tail(Y{}, k1);
+      float mx[2];
       pipe_phase_b1<PAR>(v_addr, mx);
       new_tile_max(mx, sc_t[1 - PAR]);
-#ifdef PIPE_DEBUG_NO_B2K
-      if (i + 3 < n) {
-        issue_k(i + 3);
-        pipe_phase_b2<PAR>(v_addr, sc_t[1 - PAR], m_ref, l0, l1);
-        wait_tiles(2);
-      } else
-#endif
-      if (i + 3 < n) {
-        pipe_phase_b2_k<PAR>(v_addr, sc_t[1 - PAR], m_ref, l0, l1, Kres, k_lane_off, (uint32_t)c3 * (BK * ROWB),
+      if (i + 3 < T) {
+        pipe_phase_b2_k<PAR>(v_addr, sc_t[1 - PAR], m_ref, l, Kres, k_lane_off0, k_lane_off1, (uint32_t)k3 * ROWB,
                              lds_wave + (1 - PAR) * TILE);
         wait_tiles(2);  // K_{i+2} landed; V_{i+1}, K_{i+3} may be in flight
       } else {
-        pipe_phase_b2<PAR>(v_addr, sc_t[1 - PAR], m_ref, l0, l1);
+        pipe_phase_b2<PAR>(v_addr, sc_t[1 - PAR], m_ref, l);
         wait_tiles(1);  // K_{i+2} landed (if any); V_{i+1} may be in flight
       }
       pipe_barrier();
     };
-    // The last tile: nothing left to overlap with.
+    // The last sub-tile: nothing left to overlap with.
     auto stage_last = [&](auto par) {
       constexpr int PAR = decltype(par)::value;
       rescale_o_if_pending();
-      pipe_softmax_part1<PAR>(sc_t[PAR], m_ref, l0, l1);
+      pipe_softmax_part1<PAR>(sc_t[PAR], m_ref, l);
       wait_vmem<0>();
       pipe_barrier();
       pipe_pv_plain<PAR>(v_addr);
+      pipe_barrier();  // the other wavefront has read its last V operands: the buffers may be reused
     };
 
     using T0 = std::integral_constant<int, 0>;
     using T1 = std::integral_constant<int, 1>;
-    if (n > 0) {
-      // ---- prologue: S_0, its maximum, first part of P_0
+    if (T > 0) {
+      // ---- prologue: S_0, its maxima, first part of P_0
       wait_vmem<0>();
       pipe_barrier();  // every wave's share of K_0, V_0, K_1 has landed
       pipe_qk_first(k_addr);
       pipe_barrier();  // K buffer 0 is free again
-      if (n > 2) issue_k(2);
-      mask_if_tail(T0{}, col(0));
-      float mx;
+      if (T > 2) issue_k(2);
+      mask_if_tail(T0{}, first_key_s(0));
+      float mx[2];
       pipe_max_plain<0>(mx);
       new_tile_max(mx, sc_t[0]);
-      alpha_o = 1.0f;  // O is still zero: nothing to rescale for the first maximum
-      pipe_softmax_part0<0>(sc_t[0], m_ref, l0, l1);
-      // kv blocks of the next tiles, kept in scalar registers; the LDS read of the entry
+      alpha_o[0] = alpha_o[1] = 1.0f;  // O is still zero: nothing to rescale for the first maxima
+      pipe_softmax_part0<0>(sc_t[0], m_ref, l);
+      // first keys of the next sub-tiles, kept in scalar registers; the LDS read of the entry
       // needed two steps later is issued one step ahead of its use
-      auto colc = [&](int t) { return colbuf[t < n ? t : n - 1]; };
-      int c1 = __builtin_amdgcn_readfirstlane(colc(1)), c2 = __builtin_amdgcn_readfirstlane(colc(2));
-      int c3 = __builtin_amdgcn_readfirstlane(colc(3));
-      int pend = colc(4);
+      auto keyc = [&](int t) { return first_key(t < T ? t : T - 1); };
+      int k1 = __builtin_amdgcn_readfirstlane(keyc(1)), k2 = __builtin_amdgcn_readfirstlane(keyc(2));
+      int k3 = __builtin_amdgcn_readfirstlane(keyc(3));
+      int pend = keyc(4);
       auto advance = [&](int i) {
-        c1 = c2;
-        c2 = c3;
-        c3 = __builtin_amdgcn_readfirstlane(pend);
-        pend = colc(i + 5);
+        k1 = k2;
+        k2 = k3;
+        k3 = __builtin_amdgcn_readfirstlane(pend);
+        pend = keyc(i + 5);
       };
       int i = 0;
-      for (; i + 2 < n; i += 2) {
-        stage_full(T0{}, i, c1, c3);
+      for (; i + 2 < T; i += 2) {
+        stage_full(T0{}, i, k1, k3);
         advance(i);
-        stage_full(T1{}, i + 1, c1, c3);
+        stage_full(T1{}, i + 1, k1, k3);
         advance(i + 1);
       }
-      if (n - i == 2) {
-        stage_full(T0{}, i, c1, c3);
+      if (T - i == 2) {
+        stage_full(T0{}, i, k1, k3);
         stage_last(T1{});
       } else {
         stage_last(T0{});
       }
     }
 
-    // ---- normalise, stage in LDS (K buffers), store to the block and its repeat targets
-    const float l_tot = sum_with_other_half(l0 + l1);
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    pipe_store_o(inv, o_addr);
+    // ---- normalise, stage in LDS (K and V buffers), store to the block and its repeat targets
+    const float l_tot0 = sum_with_other_half(l[0][0] + l[0][1]), l_tot1 = sum_with_other_half(l[1][0] + l[1][1]);
+    pipe_store_o<0>(l_tot0 > 0.f ? 1.0f / l_tot0 : 0.f, o_addr0);
+    pipe_store_o<1>(l_tot1 > 0.f ? 1.0f / l_tot1 : 0.f, o_addr1);
     __syncthreads();
     const int fbeg = fan_ptr[item];
     const int fend = fan_ptr[item + 1];

@@ -4,19 +4,21 @@
 Run after changing anything here:  python3 gen_pipe_asm.py   (the header is
 committed; the build does not run this script).
 
-The pipelined kernel keeps its large operands in registers the compiler is told
-never to touch (the kernel is compiled with a cap of 64 vector registers), so
-every instruction that reads or writes them is emitted here with literal
-register names:
+A wavefront of the pipelined kernel owns 64 queries (two groups qg of 32) and
+works on kv sub-tiles of 64 keys (two sub-blocks kb of 32).  Its large operands
+live in registers the compiler is told never to touch (the kernel is compiled
+with a cap of 64 vector registers and must not spill beyond a15, which the
+build checks), so every instruction that reads or writes them is emitted here
+with literal register names:
 
-  v[64:127]   S of even tiles   S[t][kb][v]: 4 key sub-blocks x 16 accumulators
-  v[128:191]  S of odd tiles
-  v[192:223]  P of even tiles   32 registers = 32 bf16 pairs, pair pi = logits 2pi, 2pi+1
-  v[224:255]  P of odd tiles
-  a[64:95]    K operands of one k-slab, two stages of 4 key sub-blocks x 4 registers
-  a[96:127]   V^T operands of one 16-key slab, two stages of 4 d blocks x 4 registers
-  a[128:191]  O^T: 4 d blocks x 16 accumulators
-  a[192:223]  Q^T: 8 k-slabs x 4 registers
+  v[64:127]   S of even sub-tiles  S[t][kb][qg][16 accumulators]
+  v[128:191]  S of odd sub-tiles
+  v[192:223]  P of even sub-tiles  P[t][kb][qg][8]: register r = bf16 pair of logits 2r, 2r+1
+  v[224:255]  P of odd sub-tiles
+  a[16:31]    K operands of one k-slab, two stages of 2 key sub-blocks x 4 registers
+  a[32:63]    V^T operands of one 16-key slab, two stages of 4 d blocks x 4 registers
+  a[64:127]   Q^T: 8 k-slabs x 2 query groups x 4 registers
+  a[128:255]  O^T: 4 d blocks x 2 query groups x 16 accumulators
 
 Hazards the assembler does not check and that the streams below respect:
   * a transcendental result is not read by the next instruction;
@@ -27,50 +29,54 @@ Hazards the assembler does not check and that the streams below respect:
 """
 import os
 
-FB_PAIRS = 12  # pairs of a tile's logits whose softmax rides on the PV product (the rest rides on QK)
+EXP = set(os.environ.get("PIPE_GEN_EXP", "").split(","))  # timing experiments only: nolds, novalu, nodma
+FB_PAIRS = 13  # pairs of a sub-tile's logits whose softmax rides on the PV product (the rest rides on QK)
 
 
-def S(t, idx):
-    return f"v{64 + 64 * t + idx}"
+def S(t, kb, qg, v):
+    return f"v{64 + 64 * t + 32 * kb + 16 * qg + v}"
 
 
-def St(t, kb):
-    b = 64 + 64 * t + 16 * kb
+def St(t, kb, qg):
+    b = 64 + 64 * t + 32 * kb + 16 * qg
     return f"v[{b}:{b + 15}]"
 
 
-def Pr(t, pi):
-    return f"v{192 + 32 * t + pi}"
+def Pr(t, kb, qg, r):
+    return f"v{192 + 32 * t + 16 * kb + 8 * qg + r}"
 
 
-def Pt(t, j):  # B operand of 16-key slab j
-    b = 192 + 32 * t + 4 * j
+def Pt(t, j, qg):  # B operand of 16-key slab j
+    b = 192 + 32 * t + 16 * (j >> 1) + 8 * qg + 4 * (j & 1)
     return f"v[{b}:{b + 3}]"
 
 
 def Ka(st, kb):
-    b = 64 + 16 * st + 4 * kb
+    b = 16 + 8 * st + 4 * kb
     return f"a[{b}:{b + 3}]"
 
 
 def Va(st, db, half):
-    b = 96 + 16 * st + 4 * db + 2 * half
+    b = 32 + 16 * st + 4 * db + 2 * half
     return f"a[{b}:{b + 1}]"
 
 
 def Vt(st, db):
-    b = 96 + 16 * st + 4 * db
+    b = 32 + 16 * st + 4 * db
     return f"a[{b}:{b + 3}]"
 
 
-def Ot(db):
-    b = 128 + 16 * db
-    return f"a[{b}:{b + 15}]"
-
-
-def Qt(s):
-    b = 192 + 4 * s
+def Qt(s, qg):
+    b = 64 + 8 * s + 4 * qg
     return f"a[{b}:{b + 3}]"
+
+
+def O(db, qg, i=0):
+    return 128 + 32 * db + 16 * qg + i
+
+
+def Ot(db, qg):
+    return f"a[{O(db, qg)}:{O(db, qg) + 15}]"
 
 
 class Op:
@@ -78,43 +84,54 @@ class Op:
         self.text, self.slots, self.trans_dst, self.reads = text, slots, trans_dst, tuple(reads)
 
 
+def pair(p):
+    """Pair p of a sub-tile in the order the PV slabs consume them: (kb, qg, r)."""
+    j, qg, r4 = p // 8, (p % 8) // 4, p % 4
+    return j >> 1, qg, 4 * (j & 1) + r4
+
+
 def softmax_ops(t, pairs):
-    """exp2(sc * s - m) of the given logit pairs of tile t, rounded to bf16 into P,
-    row sums of the rounded values into l0 / l1.  Software-pipelined by one pair."""
+    """exp2(sc * s - m) of the given logit pairs of sub-tile t, rounded to bf16 into P,
+    row sums of the rounded values into l<qg>0 / l<qg>1.  Software-pipelined by one pair."""
     ops = []
     prev = None
-    for n, pi in enumerate(pairs):
+    for n, p in enumerate(pairs):
+        kb, qg, r = pair(p)
         ta, tb = f"%[t{2 * (n % 2)}]", f"%[t{2 * (n % 2) + 1}]"
-        ops.append(Op(f"v_fma_f32 {ta}, {S(t, 2 * pi)}, %[sc], -%[m]"))
-        ops.append(Op(f"v_fma_f32 {tb}, {S(t, 2 * pi + 1)}, %[sc], -%[m]"))
+        ops.append(Op(f"v_fma_f32 {ta}, {S(t, kb, qg, 2 * r)}, %[sc], -%[mq{qg}]"))
+        ops.append(Op(f"v_fma_f32 {tb}, {S(t, kb, qg, 2 * r + 1)}, %[sc], -%[mq{qg}]"))
         if prev:
             ops += finish_pair(t, *prev)
         ops.append(Op(f"v_exp_f32 {ta}, {ta}", 2, trans_dst=ta))
         ops.append(Op(f"v_exp_f32 {tb}, {tb}", 2, trans_dst=tb))
-        prev = (pi, ta, tb)
+        prev = (p, ta, tb)
     if prev:
         ops.append(Op("s_nop 0"))
         ops += finish_pair(t, *prev)
-        ops.append(Op("s_nop 3"))  # the compiler may touch l0 / l1 right after the block
+        ops.append(Op("s_nop 3"))  # the compiler may touch the row sums right after the block
     return ops
 
 
-def finish_pair(t, pi, ta, tb):
-    return [Op(f"v_cvt_pk_bf16_f32 {Pr(t, pi)}, {ta}, {tb}", reads=(ta, tb)),
-            Op(f"v_dot2c_f32_bf16 %[l{pi % 2}], 0x3f803f80, {Pr(t, pi)}")]
+def finish_pair(t, p, ta, tb):
+    kb, qg, r = pair(p)
+    return [Op(f"v_cvt_pk_bf16_f32 {Pr(t, kb, qg, r)}, {ta}, {tb}", reads=(ta, tb)),
+            Op(f"v_dot2c_f32_bf16 %[l{qg}{p % 2}], 0x3f803f80, {Pr(t, kb, qg, r)}")]
 
 
 def max_ops(t):
-    """Maximum of this lane's 64 logits of tile t into %[mx] (uses %[t0])."""
-    ops = [Op(f"v_max3_f32 %[mx], {S(t, 0)}, {S(t, 1)}, {S(t, 2)}"),
-           Op(f"v_max3_f32 %[t0], {S(t, 3)}, {S(t, 4)}, {S(t, 5)}")]
-    acc = ["%[mx]", "%[t0]"]
-    i, k = 6, 0
-    while i < 64:
-        ops.append(Op(f"v_max3_f32 {acc[k]}, {S(t, i)}, {S(t, i + 1)}, {acc[k]}"))
-        i += 2
-        k ^= 1
-    ops.append(Op("v_max_f32 %[mx], %[mx], %[t0]"))
+    """Maxima of this lane's 32 logits per query group of sub-tile t into %[mx0], %[mx1] (use %[t0], %[t1])."""
+    ops = []
+    for qg in range(2):
+        vals = [S(t, kb, qg, v) for kb in range(2) for v in range(16)]
+        acc = [f"%[mx{qg}]", f"%[t{qg}]"]
+        ops.append(Op(f"v_max3_f32 {acc[0]}, {vals[0]}, {vals[1]}, {vals[2]}"))
+        ops.append(Op(f"v_max3_f32 {acc[1]}, {vals[3]}, {vals[4]}, {vals[5]}"))
+        i, k = 6, 0
+        while i < 32:
+            ops.append(Op(f"v_max3_f32 {acc[k]}, {vals[i]}, {vals[i + 1]}, {acc[k]}"))
+            i += 2
+            k ^= 1
+        ops.append(Op(f"v_max_f32 {acc[0]}, {acc[0]}, {acc[1]}"))
     return ops
 
 
@@ -148,12 +165,13 @@ def weave(anchors, valu, pre=0):
 
 
 def dma(j):
-    return [f"s_add_u32 m0, %[dl], {j * 4096}", f"s_add_u32 %[st], %[ds], {j * 4096}",
-            "buffer_load_dwordx4 %[dv], %[dr], %[st] offen lds"]
+    """One 1 KB direct-to-LDS load of a wave: 4 rows of the sub-tile, 8 per wave and sub-tile."""
+    return [f"s_add_u32 m0, %[dl], {j * 2048}", f"s_add_u32 %[st], %[ds], {j * 2048}",
+            f"buffer_load_dwordx4 %[dv{j & 1}], %[dr], %[st] offen lds"]
 
 
 def k_reads(st, s, koff):
-    return [f"ds_read_b128 {Ka(st, kb)}, %[ka{s}] offset:{koff + kb * 8192}" for kb in range(4)]
+    return [f"ds_read_b128 {Ka(st, kb)}, %[ka{s}] offset:{koff + kb * 8192}" for kb in range(2)]
 
 
 def v_reads(st, j, voff):
@@ -169,59 +187,77 @@ def qk_anchors(ty, koff, with_dma):
     anchors = []
     for s in range(8):
         st = s & 1
-        for kb in range(4):
+        for n, (kb, qg) in enumerate(((0, 0), (0, 1), (1, 0), (1, 1))):
             before, after = [], []
-            if kb == 0:
+            if n == 0:
                 if s < 7:
                     before += k_reads(1 - st, s + 1, koff)
-                    before.append("s_waitcnt lgkmcnt(4)")
+                    before.append("s_waitcnt lgkmcnt(2)")
                 else:
                     before.append("s_waitcnt lgkmcnt(0)")
-            c = "0" if s == 0 else St(ty, kb)
-            mfma = f"v_mfma_f32_32x32x16_bf16 {St(ty, kb)}, {Ka(st, kb)}, {Qt(s)}, {c}"
-            if with_dma and kb == 1:
+            c = "0" if s == 0 else St(ty, kb, qg)
+            mfma = f"v_mfma_f32_32x32x16_bf16 {St(ty, kb, qg)}, {Ka(st, kb)}, {Qt(s, qg)}, {c}"
+            if with_dma and n == 1:
                 after += dma(s)
             anchors.append((before, mfma, after))
     return anchors
 
 
-def pv_anchors(tx, voff, slabs, dma_plan=None):
-    """16-key slabs of O^T += V^T P_tx; operands of slab j+2 are read once slab j has issued."""
+def pv_anchors(tx, voff, slabs, dma_at=()):
+    """16-key slabs of O^T += V^T P_tx; operands of slab j+1 are read while slab j multiplies."""
     anchors = []
     for j in slabs:
         st = j & 1
-        for db in range(4):
+        for n, (db, qg) in enumerate((db, qg) for db in range(4) for qg in range(2)):
             before, after = [], []
-            if db == 0:
-                before.append("s_waitcnt lgkmcnt(8)" if j < 7 else "s_waitcnt lgkmcnt(0)")
-            mfma = f"v_mfma_f32_32x32x16_bf16 {Ot(db)}, {Vt(st, db)}, {Pt(tx, j)}, {Ot(db)}"
-            if dma_plan and (j, db) in dma_plan:
-                after += dma(dma_plan[(j, db)])
-            if db == 3 and j + 2 < 8:
-                after += v_reads(st, j + 2, voff)
+            if n == 0:
+                if j < 3:
+                    before += v_reads(1 - st, j + 1, voff)
+                    before.append("s_waitcnt lgkmcnt(8)")
+                else:
+                    before.append("s_waitcnt lgkmcnt(0)")
+            mfma = f"v_mfma_f32_32x32x16_bf16 {Ot(db, qg)}, {Vt(st, db)}, {Pt(tx, j, qg)}, {Ot(db, qg)}"
             anchors.append((before, mfma, after))
+    for d, a in enumerate(dma_at):
+        anchors[a][2].extend(dma(d))
     return anchors
 
 
-ALL_CLOBBERS = ", ".join([f'"v{i}"' for i in range(64, 256)] + [f'"a{i}"' for i in range(64, 224)])
+ALL_CLOBBERS = ", ".join([f'"v{i}"' for i in range(64, 256)] + [f'"a{i}"' for i in range(16, 256)])
 
 T4_OUT = '[t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3)'
-SM_OUT = f'{T4_OUT}, [l0] "+v"(l0), [l1] "+v"(l1)'
-SM_IN = '[sc] "v"(sc), [m] "v"(m)'
+L_OUT = '[l00] "+v"(l[0][0]), [l01] "+v"(l[0][1]), [l10] "+v"(l[1][0]), [l11] "+v"(l[1][1])'
+SM_OUT = f'{T4_OUT}, {L_OUT}'
+SM_IN = '[sc] "v"(sc), [mq0] "v"(m[0]), [mq1] "v"(m[1])'
+SM_SIG = "float sc, const float (&m)[2], float (&l)[2][2]"
 DMA_OUT = '[st] "=&s"(st)'
-DMA_IN = '[dr] "s"(rsrc), [dv] "v"(lane_off), [ds] "s"(soff), [dl] "s"(lds)'
-DMA_SIG = "const u32x4 &rsrc, uint32_t lane_off, uint32_t soff, uint32_t lds"
+DMA_IN = '[dr] "s"(rsrc), [dv0] "v"(lane_off0), [dv1] "v"(lane_off1), [ds] "s"(soff), [dl] "s"(lds)'
+DMA_SIG = "const u32x4 &rsrc, uint32_t lane_off0, uint32_t lane_off1, uint32_t soff, uint32_t lds"
+MX_OUT = '[mx0] "=&v"(mx[0]), [mx1] "=&v"(mx[1]), [t0] "=&v"(t0), [t1] "=&v"(t1)'
 
 
 def emit(lines, outs, ins, extra_clobbers=""):
+    if "nolds" in EXP:
+        lines = [l for l in lines if not l.startswith("ds_read")]
+    if "nodma" in EXP:
+        lines = [l for l in lines if not l.startswith("buffer_load")]
+    if "novalu" in EXP:
+        lines = [l for l in lines if not l.startswith(("v_fma", "v_exp", "v_cvt", "v_dot2c", "v_max"))]
     body = "\n".join(f'        "{l}\\n\\t"' for l in lines)
     return f"    asm volatile(\n{body}\n        : {outs}\n        : {ins}\n        : PIPE_PINNED{extra_clobbers});\n"
 
 
-def by_parity(sig, pre, make):
-    out = f"template <int PAR>\n__device__ __forceinline__ void {sig} {{\n{pre}"
-    out += "  if constexpr (PAR == 0) {\n" + make(0) + "  } else {\n" + make(1) + "  }\n}\n\n"
+def by_index(tparam, count, sig, pre, make):
+    out = f"template <int {tparam}>\n__device__ __forceinline__ void {sig} {{\n{pre}"
+    for i in range(count):
+        kw = "if" if i == 0 else "} else if"
+        out += f"  {kw} constexpr ({tparam} == {i}) {{\n" + make(i)
+    out += "  }\n}\n\n"
     return out
+
+
+def by_parity(sig, pre, make):
+    return by_index("PAR", 2, sig, pre, make)
 
 
 def main():
@@ -231,113 +267,114 @@ def main():
              "// respected are described at the top of the script and in attn_kernel_pipe.h.\n"
              "#pragma once\n#include \"attn_common.h\"\n\nnamespace calibatt_dev {\n\n")
     o.append(f"#define PIPE_PINNED {ALL_CLOBBERS}\n\n")
-    o.append(f"constexpr int PIPE_FB_PAIRS = {FB_PAIRS};\n\n")
 
     # ---- O = 0
-    lines = [f"v_accvgpr_write_b32 a{128 + i}, 0" for i in range(64)]
-    o.append("__device__ __forceinline__ void pipe_zero_o() {\n" + emit(lines, "", "")  + "}\n\n")
+    lines = [f"v_accvgpr_write_b32 a{128 + i}, 0" for i in range(128)]
+    o.append("__device__ __forceinline__ void pipe_zero_o() {\n" + emit(lines, "", "") + "}\n\n")
 
-    # ---- Q^T -> a[192:223], four k-slabs per call
-    def loadq(half):
+    # ---- Q^T -> a[64:127], two k-slabs (x two query groups) per call
+    def loadq(part):
         lines = []
-        for s in range(4):
+        for n, (s, qg) in enumerate((s, qg) for s in (2 * part, 2 * part + 1) for qg in range(2)):
             for e in range(4):
-                lines.append(f"v_accvgpr_write_b32 a{192 + 16 * half + 4 * s + e}, %[q{s}{e}]")
-        ins = ", ".join(f'[q{s}{e}] "v"(q{s}[{e}])' for s in range(4) for e in range(4))
+                lines.append(f"v_accvgpr_write_b32 a{64 + 8 * s + 4 * qg + e}, %[q{n}{e}]")
+        ins = ", ".join(f'[q{n}{e}] "v"(q{n}[{e}])' for n in range(4) for e in range(4))
         return emit(lines, "", ins)
-    o.append("template <int PAR>\n__device__ __forceinline__ void pipe_load_q(const u32x4 &q0, const u32x4 &q1, const u32x4 &q2, const u32x4 &q3) {\n"
-             "  if constexpr (PAR == 0) {\n" + loadq(0) + "  } else {\n" + loadq(1) + "  }\n}\n\n")
+    o.append(by_index("PART", 4, "pipe_load_q(const u32x4 &q0, const u32x4 &q1, const u32x4 &q2, const u32x4 &q3)", "", loadq))
 
-    # ---- O *= alpha
-    lines = ["s_nop 15"]
-    for i in range(0, 64, 4):
-        lines += [f"v_accvgpr_read_b32 %[t{e}], a{128 + i + e}" for e in range(4)]
-        lines += [f"v_mul_f32 %[t{e}], %[al], %[t{e}]" for e in range(4)]
-        lines += [f"v_accvgpr_write_b32 a{128 + i + e}, %[t{e}]" for e in range(4)]
-    lines.append("s_nop 7")
-    o.append("__device__ __forceinline__ void pipe_rescale_o(float alpha) {\n  float t0, t1, t2, t3;\n" +
-             emit(lines, T4_OUT, '[al] "v"(alpha)') + "}\n\n")
+    # ---- O *= alpha, one query group
+    def rescale(qg):
+        lines = ["s_nop 15"]
+        regs = [O(db, qg, i) for db in range(4) for i in range(16)]
+        for i in range(0, 64, 4):
+            lines += [f"v_accvgpr_read_b32 %[t{e}], a{regs[i + e]}" for e in range(4)]
+            lines += [f"v_mul_f32 %[t{e}], %[al], %[t{e}]" for e in range(4)]
+            lines += [f"v_accvgpr_write_b32 a{regs[i + e]}, %[t{e}]" for e in range(4)]
+        lines.append("s_nop 7")
+        return emit(lines, T4_OUT, '[al] "v"(alpha)')
+    o.append(by_index("QG", 2, "pipe_rescale_o(float alpha)", "  float t0, t1, t2, t3;\n", rescale))
 
-    # ---- O / l -> bf16 -> LDS staging row (lane: query row, 8-byte pieces at 64 db + 16 a)
-    lines = ["s_nop 15"]
-    for db in range(4):
-        for a in range(4):
-            lines += [f"v_accvgpr_read_b32 %[t{e}], a{128 + 16 * db + 4 * a + e}" for e in range(4)]
-            lines += [f"v_mul_f32 %[t{e}], %[inv], %[t{e}]" for e in range(4)]
-            w = 64 + 2 * ((4 * db + a) % 8)  # S registers are free by now; a pair is reused 8 stores later
-            lines += [f"v_cvt_pk_bf16_f32 v{w}, %[t0], %[t1]", f"v_cvt_pk_bf16_f32 v{w + 1}, %[t2], %[t3]",
-                      f"ds_write_b64 %[ad], v[{w}:{w + 1}] offset:{64 * db + 16 * a}"]
-    lines.append("s_waitcnt lgkmcnt(0)")
-    o.append("__device__ __forceinline__ void pipe_store_o(float inv, uint32_t ad) {\n  float t0, t1, t2, t3;\n" +
-             emit(lines, T4_OUT, '[inv] "v"(inv), [ad] "v"(ad)') + "}\n\n")
+    # ---- O / l -> bf16 -> LDS staging row of one query group (8-byte pieces at 64 db + 16 a)
+    def store(qg):
+        lines = ["s_nop 15"]
+        for db in range(4):
+            for a in range(4):
+                lines += [f"v_accvgpr_read_b32 %[t{e}], a{O(db, qg, 4 * a + e)}" for e in range(4)]
+                lines += [f"v_mul_f32 %[t{e}], %[inv], %[t{e}]" for e in range(4)]
+                w = 64 + 2 * ((4 * db + a) % 8)  # S registers are free by now; a pair is reused 8 stores later
+                lines += [f"v_cvt_pk_bf16_f32 v{w}, %[t0], %[t1]", f"v_cvt_pk_bf16_f32 v{w + 1}, %[t2], %[t3]",
+                          f"ds_write_b64 %[ad], v[{w}:{w + 1}] offset:{64 * db + 16 * a}"]
+        lines.append("s_waitcnt lgkmcnt(0)")
+        return emit(lines, T4_OUT, '[inv] "v"(inv), [ad] "v"(ad)')
+    o.append(by_index("QG", 2, "pipe_store_o(float inv, uint32_t ad)", "  float t0, t1, t2, t3;\n", store))
 
-    # ---- row maximum of tile T without a partner product (first tile)
-    o.append(by_parity("pipe_max_plain(float &mx)", "  float t0;\n",
-                       lambda t: emit(["s_nop 15"] + [x.text for x in max_ops(t)], '[mx] "=&v"(mx), [t0] "=&v"(t0)', "")))
+    # ---- row maxima of sub-tile PAR without a partner product (first sub-tile)
+    o.append(by_parity("pipe_max_plain(float (&mx)[2])", "  float t0, t1;\n",
+                       lambda t: emit(["s_nop 15"] + [x.text for x in max_ops(t)], MX_OUT, "")))
 
-    # ---- ragged last kv block: S = key < N ? S * sc : -inf  (lim = N - first key of this lane's group)
+    # ---- ragged end of the sequence: S = key < N ? S * sc : -inf  (lim = N - first key of this lane's group)
     def mask(t):
         lines = ["s_nop 15"]
-        for kb in range(4):
-            for v in range(16):
-                kidx = 32 * kb + 16 * (v >> 3) + (v & 7)
-                r = S(t, 16 * kb + v)
-                lines += [f"v_mul_f32 {r}, %[sc], {r}", f"v_cmp_lt_i32 vcc, {kidx}, %[lim]", f"v_cndmask_b32 {r}, %[ninf], {r}, vcc"]
+        for kb in range(2):
+            for qg in range(2):
+                for v in range(16):
+                    kidx = 32 * kb + 16 * (v >> 3) + (v & 7)
+                    r = S(t, kb, qg, v)
+                    lines += [f"v_mul_f32 {r}, %[sc], {r}", f"v_cmp_lt_i32 vcc, {kidx}, %[lim]", f"v_cndmask_b32 {r}, %[ninf], {r}, vcc"]
         return emit(lines, "", '[sc] "v"(sc), [lim] "v"(lim), [ninf] "v"(ninf)', ', "vcc"')
     o.append(by_parity("pipe_mask_tail(float sc, int lim, float ninf)", "", mask))
 
-    # ---- softmax of part of tile T without a partner product (first and last tile)
+    # ---- softmax of part of sub-tile PAR without a partner product (first and last sub-tile)
     for part, (lo, hi) in enumerate([(0, FB_PAIRS), (FB_PAIRS, 32)]):
         def sm(t, lo=lo, hi=hi):
             ops = softmax_ops(t, range(lo, hi))
             check_trans(ops)
-            lines = [x.text for x in ops]
-            return emit(lines, SM_OUT, SM_IN)
-        o.append(by_parity(f"pipe_softmax_part{part}(float sc, float m, float &l0, float &l1)", "  float t0, t1, t2, t3;\n", sm))
+            return emit([x.text for x in ops], SM_OUT, SM_IN)
+        o.append(by_parity(f"pipe_softmax_part{part}({SM_SIG})", "  float t0, t1, t2, t3;\n", sm))
 
-    # ---- S_0 = K_0 Q^T (first tile, K buffer 0)
+    # ---- S_0 = K_0 Q^T (first sub-tile, K buffer 0)
     lines = k_reads(0, 0, 0) + weave(qk_anchors(0, 0, False), []) + ["s_nop 15"]
     ka_in = ", ".join(f'[ka{s}] "v"(ka[{s}])' for s in range(8))
     o.append("__device__ __forceinline__ void pipe_qk_first(const uint32_t (&ka)[8]) {\n" + emit(lines, "", ka_in) + "}\n\n")
 
-    # ---- phase A(i), PAR = i & 1: S_{i+1} = K_{i+1} Q^T | softmax of the later pairs of tile i | DMA of V_{i+1}
+    # ---- phase A(i), PAR = i & 1: S_{i+1} = K_{i+1} Q^T | softmax of the later pairs of sub-tile i | DMA of V_{i+1}
     def phase_a(par):
         x, y = par, 1 - par
-        koff = (1 - par) * 32768
+        koff = (1 - par) * 16384
         valu = softmax_ops(x, range(FB_PAIRS, 32))
         lines = k_reads(0, 0, koff) + weave(qk_anchors(y, koff, True), valu, pre=10)
         return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{ka_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"')
-    o.append(by_parity(f"pipe_phase_a(const uint32_t (&ka)[8], float sc, float m, float &l0, float &l1, {DMA_SIG})",
+    o.append(by_parity(f"pipe_phase_a(const uint32_t (&ka)[8], {SM_SIG}, {DMA_SIG})",
                        "  float t0, t1, t2, t3;\n  uint32_t st;\n", phase_a))
 
     va_in = ", ".join(f'[va{d}] "v"(va[{d}])' for d in range(4))
 
-    # ---- phase B1(i): first two slabs of O += V_i^T P_i | row maximum of S_{i+1}
+    # ---- phase B1(i): first slab of O += V_i^T P_i | row maxima of S_{i+1}
     def phase_b1(par):
         x, y = par, 1 - par
-        voff = par * 32768
-        lines = v_reads(0, 0, voff) + v_reads(1, 1, voff) + weave(pv_anchors(x, voff, (0, 1)), max_ops(y))
-        return emit(lines, '[mx] "=&v"(mx), [t0] "=&v"(t0)', va_in)
-    o.append(by_parity("pipe_phase_b1(const uint32_t (&va)[4], float &mx)", "  float t0;\n", phase_b1))
+        voff = par * 16384
+        lines = v_reads(0, 0, voff) + weave(pv_anchors(x, voff, (0,)), max_ops(y), pre=14)
+        return emit(lines, MX_OUT, va_in)
+    o.append(by_parity("pipe_phase_b1(const uint32_t (&va)[4], float (&mx)[2])", "  float t0, t1;\n", phase_b1))
 
-    # ---- phase B2(i): remaining slabs | softmax of the first pairs of tile i+1 | DMA of K_{i+3}
+    # ---- phase B2(i): remaining slabs | softmax of the first pairs of sub-tile i+1 | DMA of K_{i+3}
     def phase_b2(par, with_k):
         x, y = par, 1 - par
-        voff = par * 32768
-        plan = {(2, 1): 0, (2, 2): 1, (3, 1): 2, (3, 2): 3, (4, 1): 4, (5, 1): 5, (6, 1): 6, (7, 1): 7} if with_k else None
-        lines = weave(pv_anchors(x, voff, range(2, 8), plan), softmax_ops(y, range(0, FB_PAIRS)))
+        voff = par * 16384
+        at = (1, 4, 7, 10, 13, 16, 19, 22) if with_k else ()
+        lines = weave(pv_anchors(x, voff, (1, 2, 3), at), softmax_ops(y, range(0, FB_PAIRS)))
         if with_k:
             return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{va_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"')
         return emit(lines, SM_OUT, f"{va_in}, {SM_IN}")
-    o.append(by_parity(f"pipe_phase_b2_k(const uint32_t (&va)[4], float sc, float m, float &l0, float &l1, {DMA_SIG})",
+    o.append(by_parity(f"pipe_phase_b2_k(const uint32_t (&va)[4], {SM_SIG}, {DMA_SIG})",
                        "  float t0, t1, t2, t3;\n  uint32_t st;\n", lambda p: phase_b2(p, True)))
-    o.append(by_parity("pipe_phase_b2(const uint32_t (&va)[4], float sc, float m, float &l0, float &l1)",
+    o.append(by_parity(f"pipe_phase_b2(const uint32_t (&va)[4], {SM_SIG})",
                        "  float t0, t1, t2, t3;\n", lambda p: phase_b2(p, False)))
 
-    # ---- O += V_i^T P_i without a partner (last tile)
+    # ---- O += V_i^T P_i without a partner (last sub-tile)
     def pv_plain(par):
-        voff = par * 32768
-        lines = v_reads(0, 0, voff) + v_reads(1, 1, voff) + weave(pv_anchors(par, voff, range(8)), [])
+        voff = par * 16384
+        lines = v_reads(0, 0, voff) + weave(pv_anchors(par, voff, range(4)), [])
         return emit(lines, "", va_in)
     o.append(by_parity("pipe_pv_plain(const uint32_t (&va)[4])", "", pv_plain))
 

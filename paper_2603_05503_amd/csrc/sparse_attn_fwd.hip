@@ -76,8 +76,8 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
       static DevInfo info[64];
       constexpr int SMEM = PipeLds<D, BQ, BK>::BYTES;
       auto kernel = sparse_attn_fwd_pipe_kernel<D, BQ, BK>;
-      if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
-      return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
+      if (int st = prepare(kernel, PIPE_THREADS, SMEM, info, slots)) return st;
+      return enqueue(kernel, PIPE_THREADS, SMEM, slots, a, p, stream);
     }
   }
   constexpr int TILE_BYTES = BK * D * 2;
