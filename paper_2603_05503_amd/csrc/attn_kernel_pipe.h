@@ -40,7 +40,7 @@
 // K and V sub-tiles are double-buffered in LDS (4 x 16 KB) and arrive by
 // buffer_load ... lds issued from inside the phases, three phases ahead of
 // their first use; there are two barriers (of two wavefronts) per sub-tile.
-// The kv-block list of the row is copied to LDS once per query block.
+// The first keys of the row's sub-tiles are written to LDS once per query block.
 #pragma once
 #include <type_traits>
 
@@ -49,7 +49,7 @@
 
 namespace calibatt_dev {
 
-constexpr int PIPE_COL_CAP = 2048;  // kv-block list entries held in LDS per query block
+constexpr int PIPE_COL_CAP = 1000;  // longest kv-block list of a query block this kernel takes
 constexpr int PIPE_THREADS = 128;   // two wavefronts of 64 queries
 
 template <int D, int BQ, int BK>
@@ -58,7 +58,7 @@ struct PipeLds {
   static constexpr int TILE = SUB * D * 2;     // bytes of one K or V sub-tile
   static constexpr int MAILBOX = 4 * TILE;
   static constexpr int COLS = MAILBOX + 64;
-  static constexpr int BYTES = COLS + PIPE_COL_CAP * 4;
+  static constexpr int BYTES = COLS + (2 * PIPE_COL_CAP + 8) * 4;  // first key of every sub-tile
 };
 
 __device__ __forceinline__ void pipe_barrier() {
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
   const int N = p.N;
   const int n_items = p.n_work * p.B;
   volatile int *const mailbox = reinterpret_cast<volatile int *>(lds + Lds::MAILBOX);
-  int *const colbuf = reinterpret_cast<int *>(lds + Lds::COLS);
+  int *const keybuf = reinterpret_cast<int *>(lds + Lds::COLS);
 
   // MFMA operand addresses (see the two-workgroup kernel for the derivation); the
   // XOR swizzle makes the K address of k-slab s equal to k_addr[0] ^ (s << 5).
@@ -167,22 +167,26 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
     const int cbeg = row_ptr[id];
     const int n = row_ptr[id + 1] - cbeg;
 
-    // kv-block list of this row -> LDS (read back as wave-uniform values)
-    for (int t = tid; t < n; t += NT) colbuf[t] = col_idx[cbeg + t];
-    __syncthreads();
-    // sub-tile t = half (t & 1) of kv block colbuf[t >> 1]; T of them (the second half of a ragged
-    // last block is dropped when it holds no key)
+    // First key of every sub-tile of this row -> LDS.  Sub-tile t = half (t & 1) of kept kv block
+    // t >> 1; T of them (the second half of a ragged last block is dropped when it holds no key).
+    // Entry j holds sub-tile j + 1 (so that the pairs read in the loop are 8-byte aligned); entries
+    // past the end repeat the last sub-tile, which is what the loads issued past the end fetch.
     int T = 2 * n;
-    if (n > 0 && N - __builtin_amdgcn_readfirstlane(colbuf[n - 1]) * BK <= SUB) --T;
-    auto first_key = [&](int t) { return colbuf[t >> 1] * BK + (t & 1) * SUB; };  // wave-uniform, in a vector register
-    auto first_key_s = [&](int t) { return __builtin_amdgcn_readfirstlane(first_key(t)); };
-    auto issue_k = [&](int t) { LoadK::issue(Kres, first_key_s(t), lds_wave + (t & 1) * TILE, tid, k_lane_off0); };
-    auto issue_v = [&](int t) { LoadV::issue(Vres, first_key_s(t), lds_wave + (2 + (t & 1)) * TILE, tid, v_lane_off); };
+    if (n > 0 && N - col_idx[cbeg + n - 1] * BK <= SUB) --T;
+    for (int j = tid; j < T + 8; j += NT) {
+      const int t = j + 1 < T ? j + 1 : T - 1;
+      keybuf[j] = T > 0 ? col_idx[cbeg + (t >> 1)] * BK + (t & 1) * SUB : 0;
+    }
+    const int key_first = n > 0 ? col_idx[cbeg] * BK : 0;  // sub-tile 0
+    __syncthreads();
+    auto key_of = [&](int t) { return __builtin_amdgcn_readfirstlane(keybuf[t - 1]); };  // t >= 1
+    auto issue_k = [&](int t, int key) { LoadK::issue(Kres, key, lds_wave + (t & 1) * TILE, tid, k_lane_off0); };
+    auto issue_v = [&](int t, int key) { LoadV::issue(Vres, key, lds_wave + (2 + (t & 1)) * TILE, tid, v_lane_off); };
 
     if (T > 0) {
-      issue_k(0);
-      issue_v(0);
-      if (T > 1) issue_k(1);
+      issue_k(0, key_first);
+      issue_v(0, key_first);
+      issue_k(1, key_of(1));
     }
     // Q^T as MFMA B operand: lane (query l32 of group qg, half g) holds d = 16 s + 8 g + [0,8) of k-slab s
     {
@@ -219,30 +223,26 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
         sc_t[TP] = 1.0f;
       }
     };
-    // the (rare) move of the reference maxima, given this lane's maxima of the raw logits
-    auto new_tile_max = [&](const float (&mx)[2], float s_mul) {
-      const float m0 = max_with_other_half(mx[0] * s_mul), m1 = max_with_other_half(mx[1] * s_mul);
-      const bool up0 = m0 > m_ref[0] + RESCALE_STEP, up1 = m1 > m_ref[1] + RESCALE_STEP;
+    // the (rare) move of the reference maxima, given the row maxima of the new sub-tile
+    auto new_tile_max = [&](const float (&mx)[2]) {
+      const bool up0 = mx[0] > m_ref[0] + RESCALE_STEP, up1 = mx[1] > m_ref[1] + RESCALE_STEP;
       if (__any(up0 || up1)) {
-        const float a0 = up0 ? __builtin_amdgcn_exp2f(m_ref[0] - m0) : 1.0f;  // 0 while m_ref is still -inf
-        const float a1 = up1 ? __builtin_amdgcn_exp2f(m_ref[1] - m1) : 1.0f;
+        const float a0 = up0 ? __builtin_amdgcn_exp2f(m_ref[0] - mx[0]) : 1.0f;  // 0 while m_ref is still -inf
+        const float a1 = up1 ? __builtin_amdgcn_exp2f(m_ref[1] - mx[1]) : 1.0f;
         l[0][0] *= a0;
         l[0][1] *= a0;
         l[1][0] *= a1;
         l[1][1] *= a1;
         alpha_o[0] *= a0;
         alpha_o[1] *= a1;
-        m_ref[0] = up0 ? m0 : m_ref[0];
-        m_ref[1] = up1 ? m1 : m_ref[1];
+        m_ref[0] = up0 ? mx[0] : m_ref[0];
+        m_ref[1] = up1 ? mx[1] : m_ref[1];
       }
     };
-    auto wait_tiles = [&](int tiles_in_flight) {  // DMA of older sub-tiles has landed
-#ifdef PIPE_DEBUG_NO_VMWAIT
-      return;
+    auto wait_two_tiles = [&]() {  // all but the two youngest sub-tile loads of this wave have landed
+#ifndef PIPE_DEBUG_NO_VMWAIT
+      wait_vmem<2 * LPW>();
 #endif
-      if (tiles_in_flight >= 2) wait_vmem<2 * LPW>();
-      else if (tiles_in_flight == 1) wait_vmem<LPW>();
-      else wait_vmem<0>();
     };
     auto rescale_o_if_pending = [&]() {
       if (__any(alpha_o[0] != 1.0f || alpha_o[1] != 1.0f)) {
@@ -254,27 +254,23 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
 
     // One sub-tile step with a successor (i + 1 < T), PAR = i & 1: sub-tile i uses the S / P registers
     // and the V buffer of parity PAR, sub-tile i+1 the other ones and K buffer 1 - PAR.
-    // k1 / k3 = first key of sub-tile i+1 / i+3.
-    auto stage_full = [&](auto par, int i, int k1, int k3) {
+    // k1 / k3 = first key of sub-tile i+1 / i+3 (the last sub-tile again where there is none: the
+    // load then lands in a buffer nobody reads, and the count of loads in flight stays the same).
+    auto stage_full = [&](auto par, int k1, int k3) {
       constexpr int PAR = decltype(par)::value;
       using Y = std::integral_constant<int, 1 - PAR>;
       rescale_o_if_pending();
       pipe_phase_a<PAR>(k_addr, sc_t[PAR], m_ref, l, Vres, v_lane_off, v_lane_off, (uint32_t)k1 * ROWB,
                         lds_wave + (2 + (1 - PAR)) * TILE);
-      wait_tiles((i + 2 < T ? 1 : 0) + 1);  // V_i landed; K_{i+2}, V_{i+1} may be in flight
+      wait_two_tiles();  // V_i landed; K_{i+2}, V_{i+1} may be in flight
       pipe_barrier();
       mask_if_tail(Y{}, k1);
       float mx[2];
-      pipe_phase_b1<PAR>(v_addr, mx);
-      new_tile_max(mx, sc_t[1 - PAR]);
-      if (i + 3 < T) {
-        pipe_phase_b2_k<PAR>(v_addr, sc_t[1 - PAR], m_ref, l, Kres, k_lane_off0, k_lane_off1, (uint32_t)k3 * ROWB,
-                             lds_wave + (1 - PAR) * TILE);
-        wait_tiles(2);  // K_{i+2} landed; V_{i+1}, K_{i+3} may be in flight
-      } else {
-        pipe_phase_b2<PAR>(v_addr, sc_t[1 - PAR], m_ref, l);
-        wait_tiles(1);  // K_{i+2} landed (if any); V_{i+1} may be in flight
-      }
+      pipe_phase_b1<PAR>(v_addr, sc_t[PAR], m_ref, l, sc_t[1 - PAR], mx);
+      new_tile_max(mx);
+      pipe_phase_b2<PAR>(v_addr, sc_t[1 - PAR], m_ref, l, Kres, k_lane_off0, k_lane_off1, (uint32_t)k3 * ROWB,
+                         lds_wave + (1 - PAR) * TILE);
+      wait_two_tiles();  // K_{i+2} landed; V_{i+1}, K_{i+3} may be in flight
       pipe_barrier();
     };
     // The last sub-tile: nothing left to overlap with.
@@ -296,34 +292,28 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
       pipe_barrier();  // every wave's share of K_0, V_0, K_1 has landed
       pipe_qk_first(k_addr);
       pipe_barrier();  // K buffer 0 is free again
-      if (T > 2) issue_k(2);
-      mask_if_tail(T0{}, first_key_s(0));
+      issue_k(2, key_of(2));
+      mask_if_tail(T0{}, key_first);
       float mx[2];
-      pipe_max_plain<0>(mx);
-      new_tile_max(mx, sc_t[0]);
+      pipe_max_plain<0>(sc_t[0], mx);
+      new_tile_max(mx);
       alpha_o[0] = alpha_o[1] = 1.0f;  // O is still zero: nothing to rescale for the first maxima
       pipe_softmax_part0<0>(sc_t[0], m_ref, l);
-      // first keys of the next sub-tiles, kept in scalar registers; the LDS read of the entry
-      // needed two steps later is issued one step ahead of its use
-      auto keyc = [&](int t) { return first_key(t < T ? t : T - 1); };
-      int k1 = __builtin_amdgcn_readfirstlane(keyc(1)), k2 = __builtin_amdgcn_readfirstlane(keyc(2));
-      int k3 = __builtin_amdgcn_readfirstlane(keyc(3));
-      int pend = keyc(4);
-      auto advance = [&](int i) {
-        k1 = k2;
-        k2 = k3;
-        k3 = __builtin_amdgcn_readfirstlane(pend);
-        pend = keyc(i + 5);
-      };
+      // first keys of the next four sub-tiles, kept in scalar registers; the next two are read from
+      // LDS one loop iteration ahead of their use
+      int k1 = key_of(1), k2 = key_of(2), k3 = key_of(3), k4 = key_of(4);
       int i = 0;
       for (; i + 2 < T; i += 2) {
-        stage_full(T0{}, i, k1, k3);
-        advance(i);
-        stage_full(T1{}, i + 1, k1, k3);
-        advance(i + 1);
+        const u32x2 next = *reinterpret_cast<const u32x2 *>(keybuf + i + 4);  // sub-tiles i+5, i+6
+        stage_full(T0{}, k1, k3);
+        stage_full(T1{}, k2, k4);
+        k1 = k3;
+        k2 = k4;
+        k3 = __builtin_amdgcn_readfirstlane(next[0]);
+        k4 = __builtin_amdgcn_readfirstlane(next[1]);
       }
       if (T - i == 2) {
-        stage_full(T0{}, i, k1, k3);
+        stage_full(T0{}, k1, k3);
         stage_last(T1{});
       } else {
         stage_last(T0{});

@@ -7,7 +7,7 @@ committed; the build does not run this script).
 A wavefront of the pipelined kernel owns 64 queries (two groups qg of 32) and
 works on kv sub-tiles of 64 keys (two sub-blocks kb of 32).  Its large operands
 live in registers the compiler is told never to touch (the kernel is compiled
-with a cap of 64 vector registers and must not spill beyond a15, which the
+with a cap of 64 vector registers and must not spill beyond a7, which the
 build checks), so every instruction that reads or writes them is emitted here
 with literal register names:
 
@@ -15,7 +15,7 @@ with literal register names:
   v[128:191]  S of odd sub-tiles
   v[192:223]  P of even sub-tiles  P[t][kb][qg][8]: register r = bf16 pair of logits 2r, 2r+1
   v[224:255]  P of odd sub-tiles
-  a[16:31]    K operands of one k-slab, two stages of 2 key sub-blocks x 4 registers
+  a[8:31]     K operands of one k-slab, three stages of 2 key sub-blocks x 4 registers
   a[32:63]    V^T operands of one 16-key slab, two stages of 4 d blocks x 4 registers
   a[64:127]   Q^T: 8 k-slabs x 2 query groups x 4 registers
   a[128:255]  O^T: 4 d blocks x 2 query groups x 16 accumulators
@@ -24,13 +24,21 @@ Hazards the assembler does not check and that the streams below respect:
   * a transcendental result is not read by the next instruction;
   * MFMA results are read by other instructions only after >= 11 issue slots;
   * one instruction sits between a write of M0 and the LDS-DMA that uses it;
-  * the result of a dot instruction is not touched by an instruction of another
-    kind in the next 4 issue slots (also not by what the compiler places after a block).
+  * dot instructions are not used: they and a second transcendental between two
+    MFMAs stall the matrix pipeline, measured at about 20 cycles each, while one
+    transcendental plus up to four or five plain VALU instructions per MFMA hide
+    behind it.  The softmax is therefore laid out with exactly one v_exp_f32
+    behind every MFMA, and the row sums are plain additions of the bf16-rounded
+    probabilities, unpacked again (the sums must add exactly what the PV product
+    multiplies, or a row with one dominant key is off by the rounding of that key).
 """
 import os
 
 EXP = set(os.environ.get("PIPE_GEN_EXP", "").split(","))  # timing experiments only: nolds, novalu, nodma
-FB_PAIRS = 13  # pairs of a sub-tile's logits whose softmax rides on the PV product (the rest rides on QK)
+# Softmax of a sub-tile's 32 logit pairs, by the block whose MFMAs it hides behind (one exp per MFMA):
+PAIRS_B2 = range(0, 8)    # 16 MFMAs of the previous sub-tile's PV slabs 2-3 (these pairs feed PV slab 0)
+PAIRS_A = range(8, 24)    # 32 MFMAs of the next sub-tile's QK
+PAIRS_B1 = range(24, 32)  # 16 MFMAs of this sub-tile's PV slabs 0-1 (these pairs feed PV slab 3)
 
 
 def S(t, kb, qg, v):
@@ -52,7 +60,7 @@ def Pt(t, j, qg):  # B operand of 16-key slab j
 
 
 def Ka(st, kb):
-    b = 16 + 8 * st + 4 * kb
+    b = 8 + 8 * st + 4 * kb
     return f"a[{b}:{b + 3}]"
 
 
@@ -80,8 +88,8 @@ def Ot(db, qg):
 
 
 class Op:
-    def __init__(self, text, slots=1, trans_dst=None, reads=()):
-        self.text, self.slots, self.trans_dst, self.reads = text, slots, trans_dst, tuple(reads)
+    def __init__(self, text, trans_dst=None, reads=()):
+        self.text, self.trans_dst, self.reads = text, trans_dst, tuple(reads)
 
 
 def pair(p):
@@ -90,40 +98,58 @@ def pair(p):
     return j >> 1, qg, 4 * (j & 1) + r4
 
 
-def softmax_ops(t, pairs):
-    """exp2(sc * s - m) of the given logit pairs of sub-tile t, rounded to bf16 into P,
-    row sums of the rounded values into l<qg>0 / l<qg>1.  Software-pipelined by one pair."""
-    ops = []
-    prev = None
-    for n, p in enumerate(pairs):
-        kb, qg, r = pair(p)
-        ta, tb = f"%[t{2 * (n % 2)}]", f"%[t{2 * (n % 2) + 1}]"
-        ops.append(Op(f"v_fma_f32 {ta}, {S(t, kb, qg, 2 * r)}, %[sc], -%[mq{qg}]"))
-        ops.append(Op(f"v_fma_f32 {tb}, {S(t, kb, qg, 2 * r + 1)}, %[sc], -%[mq{qg}]"))
-        if prev:
-            ops += finish_pair(t, *prev)
-        ops.append(Op(f"v_exp_f32 {ta}, {ta}", 2, trans_dst=ta))
-        ops.append(Op(f"v_exp_f32 {tb}, {tb}", 2, trans_dst=tb))
-        prev = (p, ta, tb)
-    if prev:
-        ops.append(Op("s_nop 0"))
-        ops += finish_pair(t, *prev)
-        ops.append(Op("s_nop 3"))  # the compiler may touch the row sums right after the block
-    return ops
+def softmax_groups(t, pairs):
+    """exp2(sc * s - m) of the given logit pairs of sub-tile t, rounded to bf16 into P, row sums
+    into l<qg>0 / l<qg>1.  Returns (pre, groups, tail): two groups per pair, each starting with
+    the one transcendental it holds; pre goes before the first group, tail after the last."""
+    pairs = list(pairs)
+    n = len(pairs)
 
+    def tmp(k, w):
+        return f"%[t{2 * (k % 3) + w}]"
 
-def finish_pair(t, p, ta, tb):
-    kb, qg, r = pair(p)
-    return [Op(f"v_cvt_pk_bf16_f32 {Pr(t, kb, qg, r)}, {ta}, {tb}", reads=(ta, tb)),
-            Op(f"v_dot2c_f32_bf16 %[l{qg}{p % 2}], 0x3f803f80, {Pr(t, kb, qg, r)}")]
+    def fma(k, w):
+        kb, qg, r = pair(pairs[k])
+        return Op(f"v_fma_f32 {tmp(k, w)}, {S(t, kb, qg, 2 * r + w)}, %[sc], -%[mq{qg}]")
+
+    def exp(k, w):
+        return Op(f"v_exp_f32 {tmp(k, w)}, {tmp(k, w)}", trans_dst=tmp(k, w))
+
+    def cvt(k):
+        kb, qg, r = pair(pairs[k])
+        return Op(f"v_cvt_pk_bf16_f32 {Pr(t, kb, qg, r)}, {tmp(k, 0)}, {tmp(k, 1)}", reads=(tmp(k, 0), tmp(k, 1)))
+
+    def unpack(k, w):  # the rounded value back as fp32: the row sums add exactly what the PV product multiplies
+        kb, qg, r = pair(pairs[k])
+        if w == 0:
+            return Op(f"v_lshlrev_b32 {tmp(k, 0)}, 16, {Pr(t, kb, qg, r)}")
+        return Op(f"v_and_b32 {tmp(k, 1)}, 0xffff0000, {Pr(t, kb, qg, r)}")
+
+    def add(k, w):
+        kb, qg, r = pair(pairs[k])
+        return Op(f"v_add_f32 %[l{qg}{w}], %[l{qg}{w}], {tmp(k, w)}", reads=(tmp(k, w),))
+
+    pre = [fma(0, 0), fma(0, 1)]
+    groups = []
+    for k in range(n):
+        g0, g1 = [exp(k, 0)], [exp(k, 1)]
+        if k >= 1:
+            g0 += [cvt(k - 1), unpack(k - 1, 0)]
+            g1 += [unpack(k - 1, 1), add(k - 1, 0), add(k - 1, 1)]
+        if k + 1 < n:
+            g0.append(fma(k + 1, 0))
+            g1.append(fma(k + 1, 1))
+        groups += [g0, g1]
+    tail = [Op("s_nop 0"), cvt(n - 1), unpack(n - 1, 0), unpack(n - 1, 1), add(n - 1, 0), add(n - 1, 1)]
+    return pre, groups, tail
 
 
 def max_ops(t):
-    """Maxima of this lane's 32 logits per query group of sub-tile t into %[mx0], %[mx1] (use %[t0], %[t1])."""
+    """Maxima of this lane's 32 logits per query group of sub-tile t into %[mx0], %[mx1] (use %[xa0], %[xa1])."""
     ops = []
     for qg in range(2):
         vals = [S(t, kb, qg, v) for kb in range(2) for v in range(16)]
-        acc = [f"%[mx{qg}]", f"%[t{qg}]"]
+        acc = [f"%[mx{qg}]", f"%[xa{qg}]"]
         ops.append(Op(f"v_max3_f32 {acc[0]}, {vals[0]}, {vals[1]}, {vals[2]}"))
         ops.append(Op(f"v_max3_f32 {acc[1]}, {vals[3]}, {vals[4]}, {vals[5]}"))
         i, k = 6, 0
@@ -135,6 +161,14 @@ def max_ops(t):
     return ops
 
 
+def combine_ops():
+    """Scale the lane maxima by %[sy] and take the maximum with the other half-wave (lane ^ 32)."""
+    return [Op("v_mul_f32 %[mx0], %[sy], %[mx0]"), Op("v_mul_f32 %[mx1], %[sy], %[mx1]"),
+            Op("v_mov_b32 %[xa0], %[mx0]"), Op("v_mov_b32 %[xa1], %[mx1]"), Op("s_nop 1"),
+            Op("v_permlane32_swap_b32 %[mx0], %[xa0]"), Op("v_permlane32_swap_b32 %[mx1], %[xa1]"),
+            Op("v_max_f32 %[mx0], %[mx0], %[xa0]"), Op("v_max_f32 %[mx1], %[mx1], %[xa1]")]
+
+
 def check_trans(ops):
     """No VALU instruction reads a transcendental result in the slot right after it."""
     for a, b in zip(ops, ops[1:]):
@@ -142,26 +176,35 @@ def check_trans(ops):
             raise SystemExit(f"trans hazard: {a.text} -> {b.text}")
 
 
-def weave(anchors, valu, pre=0):
-    """anchors: list of (lines before the MFMA, MFMA line, lines after it); valu: Ops spread
-    by issue slots over the gaps after the MFMAs; the first `pre` Ops go before everything."""
-    lines = [o.text for o in valu[:pre]]
-    rest = valu[pre:]
-    total = sum(o.slots for o in rest)
+def weave(anchors, pre, groups, tail, extras=()):
+    """anchors: list of (lines before the MFMA, MFMA line, lines after it).  Gap g (behind MFMA g)
+    receives groups[g] and an even share of extras; pre goes before everything, tail at the end."""
     n = len(anchors)
-    done = 0
+    assert len(groups) <= n, (len(groups), n)
+    extras = list(extras)
+    seq = list(pre)
+    lines = [o.text for o in pre]
     k = 0
     for a, (before, mfma, after) in enumerate(anchors):
         lines += before
         lines.append(mfma)
-        goal = total * (a + 1) / n
-        while k < len(rest) and (done + rest[k].slots / 2 <= goal or a == n - 1):
-            lines.append(rest[k].text)
-            done += rest[k].slots
-            k += 1
+        gap = list(groups[a]) if a < len(groups) else []
+        goal = (len(extras) * (a + 1)) // n
+        gap += extras[k:goal]
+        k = goal
+        if a == n - 1:
+            gap += list(tail)
+        seq += gap
+        lines += [o.text for o in gap]
         lines += after
-    check_trans(valu)  # MFMAs and other instructions in between only add distance
+    check_trans(seq)  # MFMAs and other instructions in between only add distance
     return lines
+
+
+def flat(pre, groups, tail):
+    ops = list(pre) + [o for g in groups for o in g] + list(tail)
+    check_trans(ops)
+    return [o.text for o in ops]
 
 
 def dma(j):
@@ -170,8 +213,8 @@ def dma(j):
             f"buffer_load_dwordx4 %[dv{j & 1}], %[dr], %[st] offen lds"]
 
 
-def k_reads(st, s, koff):
-    return [f"ds_read_b128 {Ka(st, kb)}, %[ka{s}] offset:{koff + kb * 8192}" for kb in range(2)]
+def k_reads(s, koff):
+    return [f"ds_read_b128 {Ka(s % 3, kb)}, %[ka{s}] offset:{koff + kb * 8192}" for kb in range(2)]
 
 
 def v_reads(st, j, voff):
@@ -183,20 +226,18 @@ def v_reads(st, j, voff):
 
 
 def qk_anchors(ty, koff, with_dma):
-    """8 k-slabs of S_ty = K Q^T; operands of slab s+1 are read while slab s multiplies."""
+    """8 k-slabs of S_ty = K Q^T; operands of slab s+2 are read while slab s multiplies
+    (the caller issues the reads of slabs 0 and 1)."""
     anchors = []
     for s in range(8):
-        st = s & 1
         for n, (kb, qg) in enumerate(((0, 0), (0, 1), (1, 0), (1, 1))):
             before, after = [], []
             if n == 0:
-                if s < 7:
-                    before += k_reads(1 - st, s + 1, koff)
-                    before.append("s_waitcnt lgkmcnt(2)")
-                else:
-                    before.append("s_waitcnt lgkmcnt(0)")
+                if s + 2 < 8:
+                    before += k_reads(s + 2, koff)
+                before.append(f"s_waitcnt lgkmcnt({2 * min(2, 7 - s)})")
             c = "0" if s == 0 else St(ty, kb, qg)
-            mfma = f"v_mfma_f32_32x32x16_bf16 {St(ty, kb, qg)}, {Ka(st, kb)}, {Qt(s, qg)}, {c}"
+            mfma = f"v_mfma_f32_32x32x16_bf16 {St(ty, kb, qg)}, {Ka(s % 3, kb)}, {Qt(s, qg)}, {c}"
             if with_dma and n == 1:
                 after += dma(s)
             anchors.append((before, mfma, after))
@@ -223,26 +264,32 @@ def pv_anchors(tx, voff, slabs, dma_at=()):
     return anchors
 
 
-ALL_CLOBBERS = ", ".join([f'"v{i}"' for i in range(64, 256)] + [f'"a{i}"' for i in range(16, 256)])
+ALL_CLOBBERS = ", ".join([f'"v{i}"' for i in range(64, 256)] + [f'"a{i}"' for i in range(8, 256)])
 
 T4_OUT = '[t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3)'
+T6_OUT = T4_OUT + ', [t4] "=&v"(t4), [t5] "=&v"(t5)'
+T6_DECL = "  float t0, t1, t2, t3, t4, t5;\n"
 L_OUT = '[l00] "+v"(l[0][0]), [l01] "+v"(l[0][1]), [l10] "+v"(l[1][0]), [l11] "+v"(l[1][1])'
-SM_OUT = f'{T4_OUT}, {L_OUT}'
+SM_OUT = f'{T6_OUT}, {L_OUT}'
 SM_IN = '[sc] "v"(sc), [mq0] "v"(m[0]), [mq1] "v"(m[1])'
 SM_SIG = "float sc, const float (&m)[2], float (&l)[2][2]"
 DMA_OUT = '[st] "=&s"(st)'
 DMA_IN = '[dr] "s"(rsrc), [dv0] "v"(lane_off0), [dv1] "v"(lane_off1), [ds] "s"(soff), [dl] "s"(lds)'
 DMA_SIG = "const u32x4 &rsrc, uint32_t lane_off0, uint32_t lane_off1, uint32_t soff, uint32_t lds"
-MX_OUT = '[mx0] "=&v"(mx[0]), [mx1] "=&v"(mx[1]), [t0] "=&v"(t0), [t1] "=&v"(t1)'
+MX_OUT = '[mx0] "=&v"(mx[0]), [mx1] "=&v"(mx[1]), [xa0] "=&v"(xa0), [xa1] "=&v"(xa1)'
+MX_DECL = "  float xa0, xa1;\n"
+VALU_PREFIXES = ("v_fma", "v_exp", "v_cvt", "v_add_f32", "v_max", "v_mul", "v_mov", "v_permlane", "v_lshlrev", "v_and")
 
 
-def emit(lines, outs, ins, extra_clobbers=""):
+def emit(lines, outs, ins, extra_clobbers="", tag=""):
+    if f"novalu_{tag}" in EXP or "novalu" in EXP:
+        lines = [l for l in lines if not l.startswith(VALU_PREFIXES)]
+    if "noexp" in EXP:
+        lines = [l for l in lines if not l.startswith("v_exp")]
     if "nolds" in EXP:
         lines = [l for l in lines if not l.startswith("ds_read")]
     if "nodma" in EXP:
         lines = [l for l in lines if not l.startswith("buffer_load")]
-    if "novalu" in EXP:
-        lines = [l for l in lines if not l.startswith(("v_fma", "v_exp", "v_cvt", "v_dot2c", "v_max"))]
     body = "\n".join(f'        "{l}\\n\\t"' for l in lines)
     return f"    asm volatile(\n{body}\n        : {outs}\n        : {ins}\n        : PIPE_PINNED{extra_clobbers});\n"
 
@@ -308,9 +355,9 @@ def main():
         return emit(lines, T4_OUT, '[inv] "v"(inv), [ad] "v"(ad)')
     o.append(by_index("QG", 2, "pipe_store_o(float inv, uint32_t ad)", "  float t0, t1, t2, t3;\n", store))
 
-    # ---- row maxima of sub-tile PAR without a partner product (first sub-tile)
-    o.append(by_parity("pipe_max_plain(float (&mx)[2])", "  float t0, t1;\n",
-                       lambda t: emit(["s_nop 15"] + [x.text for x in max_ops(t)], MX_OUT, "")))
+    # ---- row maxima (scaled, combined over both half-waves) of sub-tile PAR without a partner product
+    o.append(by_parity("pipe_max_plain(float sy, float (&mx)[2])", MX_DECL,
+                       lambda t: emit(["s_nop 15"] + [x.text for x in max_ops(t) + combine_ops()], MX_OUT, '[sy] "v"(sy)')))
 
     # ---- ragged end of the sequence: S = key < N ? S * sc : -inf  (lim = N - first key of this lane's group)
     def mask(t):
@@ -325,56 +372,47 @@ def main():
     o.append(by_parity("pipe_mask_tail(float sc, int lim, float ninf)", "", mask))
 
     # ---- softmax of part of sub-tile PAR without a partner product (first and last sub-tile)
-    for part, (lo, hi) in enumerate([(0, FB_PAIRS), (FB_PAIRS, 32)]):
-        def sm(t, lo=lo, hi=hi):
-            ops = softmax_ops(t, range(lo, hi))
-            check_trans(ops)
-            return emit([x.text for x in ops], SM_OUT, SM_IN)
-        o.append(by_parity(f"pipe_softmax_part{part}({SM_SIG})", "  float t0, t1, t2, t3;\n", sm))
+    for part, prs in enumerate([PAIRS_B2, list(PAIRS_A) + list(PAIRS_B1)]):
+        o.append(by_parity(f"pipe_softmax_part{part}({SM_SIG})", T6_DECL,
+                           lambda t, prs=prs: emit(flat(*softmax_groups(t, prs)), SM_OUT, SM_IN)))
 
     # ---- S_0 = K_0 Q^T (first sub-tile, K buffer 0)
-    lines = k_reads(0, 0, 0) + weave(qk_anchors(0, 0, False), []) + ["s_nop 15"]
+    lines = k_reads(0, 0) + k_reads(1, 0) + weave(qk_anchors(0, 0, False), [], [], []) + ["s_nop 15"]
     ka_in = ", ".join(f'[ka{s}] "v"(ka[{s}])' for s in range(8))
     o.append("__device__ __forceinline__ void pipe_qk_first(const uint32_t (&ka)[8]) {\n" + emit(lines, "", ka_in) + "}\n\n")
 
-    # ---- phase A(i), PAR = i & 1: S_{i+1} = K_{i+1} Q^T | softmax of the later pairs of sub-tile i | DMA of V_{i+1}
+    # ---- phase A(i), PAR = i & 1: S_{i+1} = K_{i+1} Q^T | softmax of pairs PAIRS_A of sub-tile i | DMA of V_{i+1}
     def phase_a(par):
         x, y = par, 1 - par
         koff = (1 - par) * 16384
-        valu = softmax_ops(x, range(FB_PAIRS, 32))
-        lines = k_reads(0, 0, koff) + weave(qk_anchors(y, koff, True), valu, pre=10)
-        return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{ka_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"')
-    o.append(by_parity(f"pipe_phase_a(const uint32_t (&ka)[8], {SM_SIG}, {DMA_SIG})",
-                       "  float t0, t1, t2, t3;\n  uint32_t st;\n", phase_a))
+        lines = k_reads(0, koff) + k_reads(1, koff) + weave(qk_anchors(y, koff, True), *softmax_groups(x, PAIRS_A))
+        return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{ka_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"', tag="a")
+    o.append(by_parity(f"pipe_phase_a(const uint32_t (&ka)[8], {SM_SIG}, {DMA_SIG})", T6_DECL + "  uint32_t st;\n", phase_a))
 
     va_in = ", ".join(f'[va{d}] "v"(va[{d}])' for d in range(4))
 
-    # ---- phase B1(i): first slab of O += V_i^T P_i | row maxima of S_{i+1}
+    # ---- phase B1(i): slabs 0-1 of O += V_i^T P_i | softmax of pairs PAIRS_B1 of sub-tile i | row maxima of S_{i+1}
     def phase_b1(par):
         x, y = par, 1 - par
         voff = par * 16384
-        lines = v_reads(0, 0, voff) + weave(pv_anchors(x, voff, (0,)), max_ops(y), pre=14)
-        return emit(lines, MX_OUT, va_in)
-    o.append(by_parity("pipe_phase_b1(const uint32_t (&va)[4], float (&mx)[2])", "  float t0, t1;\n", phase_b1))
+        pre, groups, tail = softmax_groups(x, PAIRS_B1)
+        mx = max_ops(y)
+        lines = v_reads(0, 0, voff) + weave(pv_anchors(x, voff, (0, 1)), pre + mx[:8], groups, tail, mx[8:] + combine_ops())
+        return emit(lines, f"{SM_OUT}, {MX_OUT}", f"{va_in}, {SM_IN}, [sy] \"v\"(sy)", tag="b1")
+    o.append(by_parity(f"pipe_phase_b1(const uint32_t (&va)[4], {SM_SIG}, float sy, float (&mx)[2])", T6_DECL + MX_DECL, phase_b1))
 
-    # ---- phase B2(i): remaining slabs | softmax of the first pairs of sub-tile i+1 | DMA of K_{i+3}
-    def phase_b2(par, with_k):
+    # ---- phase B2(i): slabs 2-3 | softmax of pairs PAIRS_B2 of sub-tile i+1 | DMA of K_{i+3}
+    def phase_b2(par):
         x, y = par, 1 - par
         voff = par * 16384
-        at = (1, 4, 7, 10, 13, 16, 19, 22) if with_k else ()
-        lines = weave(pv_anchors(x, voff, (1, 2, 3), at), softmax_ops(y, range(0, FB_PAIRS)))
-        if with_k:
-            return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{va_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"')
-        return emit(lines, SM_OUT, f"{va_in}, {SM_IN}")
-    o.append(by_parity(f"pipe_phase_b2_k(const uint32_t (&va)[4], {SM_SIG}, {DMA_SIG})",
-                       "  float t0, t1, t2, t3;\n  uint32_t st;\n", lambda p: phase_b2(p, True)))
-    o.append(by_parity(f"pipe_phase_b2(const uint32_t (&va)[4], {SM_SIG})",
-                       "  float t0, t1, t2, t3;\n", lambda p: phase_b2(p, False)))
+        lines = weave(pv_anchors(x, voff, (2, 3), (1, 3, 5, 7, 9, 11, 13, 15)), *softmax_groups(y, PAIRS_B2))
+        return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{va_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"', tag="b2")
+    o.append(by_parity(f"pipe_phase_b2(const uint32_t (&va)[4], {SM_SIG}, {DMA_SIG})", T6_DECL + "  uint32_t st;\n", phase_b2))
 
     # ---- O += V_i^T P_i without a partner (last sub-tile)
     def pv_plain(par):
         voff = par * 16384
-        lines = v_reads(0, 0, voff) + weave(pv_anchors(par, voff, range(4)), [])
+        lines = v_reads(0, 0, voff) + weave(pv_anchors(par, voff, range(4)), [], [], [])
         return emit(lines, "", va_in)
     o.append(by_parity("pipe_pv_plain(const uint32_t (&va)[4])", "", pv_plain))
 
