@@ -16,9 +16,18 @@
 // Schedule of one query block with sub-tiles 0..T-1 (S_t = K_t Q^T, P_t =
 // exp2(sc S_t - m), O += V_t^T P_t), inside every wavefront:
 //
-//   phase A(i) : MFMA  S_{i+1} = K_{i+1} Q^T         | VALU  later part of P_i     | DMA V_{i+1}
-//   phase B1(i): MFMA  O += V_i^T P_i, first slab    | VALU  row maxima of S_{i+1}
-//   phase B2(i): MFMA  O += V_i^T P_i, other slabs   | VALU  first part of P_{i+1} | DMA K_{i+3}
+//   phase A(i) : MFMA  S_{i+1} = K_{i+1} Q^T         | VALU  middle part of P_i            | DMA V_{i+1}
+//   phase B1(i): MFMA  O += V_i^T P_i, slabs 0-1     | VALU  last part of P_i, row maxima of S_{i+1}
+//   phase B2(i): MFMA  O += V_i^T P_i, slabs 2-3     | VALU  first part of P_{i+1}         | DMA K_{i+3}
+//
+// Measured on this hardware, per MFMA of 8 passes: one transcendental and up to
+// four or five plain VALU instructions of the same wavefront cost a few cycles
+// each; a second transcendental or a dot instruction stalls the matrix pipeline
+// for about 20 cycles.  Hence exactly one v_exp_f32 behind every MFMA, and row
+// sums by plain additions.  The two workgroup barriers of a sub-tile sit inside
+// the streams, in front of the last slab of phases A and B2, and the first LDS
+// operand reads of the following phase are issued right behind them, so that
+// their latency is covered by that slab's MFMAs.
 //
 // The compiler neither interleaves MFMA and VALU streams by itself nor keeps
 // 400 live registers where they are, so S, P, O, Q and the MFMA operands live
@@ -39,7 +48,7 @@
 //
 // K and V sub-tiles are double-buffered in LDS (4 x 16 KB) and arrive by
 // buffer_load ... lds issued from inside the phases, three phases ahead of
-// their first use; there are two barriers (of two wavefronts) per sub-tile.
+// their first use.
 // The first keys of the row's sub-tiles are written to LDS once per query block.
 #pragma once
 #include <type_traits>
@@ -239,11 +248,6 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
         m_ref[1] = up1 ? mx[1] : m_ref[1];
       }
     };
-    auto wait_two_tiles = [&]() {  // all but the two youngest sub-tile loads of this wave have landed
-#ifndef PIPE_DEBUG_NO_VMWAIT
-      wait_vmem<2 * LPW>();
-#endif
-    };
     auto rescale_o_if_pending = [&]() {
       if (__any(alpha_o[0] != 1.0f || alpha_o[1] != 1.0f)) {
         pipe_rescale_o<0>(alpha_o[0]);
@@ -260,18 +264,16 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
       constexpr int PAR = decltype(par)::value;
       using Y = std::integral_constant<int, 1 - PAR>;
       rescale_o_if_pending();
-      pipe_phase_a<PAR>(k_addr, sc_t[PAR], m_ref, l, Vres, v_lane_off, v_lane_off, (uint32_t)k1 * ROWB,
+      // (barrier inside, in front of the last k-slab: V_i has landed; K_{i+2}, V_{i+1} may be in flight)
+      pipe_phase_a<PAR>(k_addr, v_addr, sc_t[PAR], m_ref, l, Vres, v_lane_off, v_lane_off, (uint32_t)k1 * ROWB,
                         lds_wave + (2 + (1 - PAR)) * TILE);
-      wait_two_tiles();  // V_i landed; K_{i+2}, V_{i+1} may be in flight
-      pipe_barrier();
       mask_if_tail(Y{}, k1);
       float mx[2];
       pipe_phase_b1<PAR>(v_addr, sc_t[PAR], m_ref, l, sc_t[1 - PAR], mx);
       new_tile_max(mx);
-      pipe_phase_b2<PAR>(v_addr, sc_t[1 - PAR], m_ref, l, Kres, k_lane_off0, k_lane_off1, (uint32_t)k3 * ROWB,
+      // (barrier inside, in front of the last slab: K_{i+2} has landed; V_{i+1}, K_{i+3} may be in flight)
+      pipe_phase_b2<PAR>(v_addr, k_addr, sc_t[1 - PAR], m_ref, l, Kres, k_lane_off0, k_lane_off1, (uint32_t)k3 * ROWB,
                          lds_wave + (1 - PAR) * TILE);
-      wait_two_tiles();  // K_{i+2} landed; V_{i+1}, K_{i+3} may be in flight
-      pipe_barrier();
     };
     // The last sub-tile: nothing left to overlap with.
     auto stage_last = [&](auto par) {
@@ -299,6 +301,7 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
       new_tile_max(mx);
       alpha_o[0] = alpha_o[1] = 1.0f;  // O is still zero: nothing to rescale for the first maxima
       pipe_softmax_part0<0>(sc_t[0], m_ref, l);
+      pipe_k_preread<1>(k_addr);  // what a phase B2 does for the phase A behind it
       // first keys of the next four sub-tiles, kept in scalar registers; the next two are read from
       // LDS one loop iteration ahead of their use
       int k1 = key_of(1), k2 = key_of(2), k3 = key_of(3), k4 = key_of(4);

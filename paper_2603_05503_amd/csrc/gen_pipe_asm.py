@@ -207,10 +207,12 @@ def flat(pre, groups, tail):
     return [o.text for o in ops]
 
 
-def dma(j):
-    """One 1 KB direct-to-LDS load of a wave: 4 rows of the sub-tile, 8 per wave and sub-tile."""
-    return [f"s_add_u32 m0, %[dl], {j * 2048}", f"s_add_u32 %[st], %[ds], {j * 2048}",
-            f"buffer_load_dwordx4 %[dv{j & 1}], %[dr], %[st] offen lds"]
+def dma_pair(j):
+    """Two 1 KB direct-to-LDS loads of a wave (instructions 2j and 2j+1 of its 8 per sub-tile): 8 rows.
+    The instruction offset moves the global and the LDS address alike, so one M0 serves both."""
+    return [f"s_add_u32 m0, %[dl], {j * 4096}", f"s_add_u32 %[st], %[ds], {j * 4096}",
+            "buffer_load_dwordx4 %[dv0], %[dr], %[st] offen lds",
+            "buffer_load_dwordx4 %[dv1], %[dr], %[st] offen offset:2048 lds"]
 
 
 def k_reads(s, koff):
@@ -225,9 +227,10 @@ def v_reads(st, j, voff):
     return out
 
 
-def qk_anchors(ty, koff, with_dma):
-    """8 k-slabs of S_ty = K Q^T; operands of slab s+2 are read while slab s multiplies
-    (the caller issues the reads of slabs 0 and 1)."""
+def qk_anchors(ty, koff, dma_at=(), sync=()):
+    """8 k-slabs of S_ty = K Q^T; operands of slab s+2 are read while slab s multiplies (the
+    reads of slabs 0 and 1 are issued before).  sync: instructions placed in front of the last
+    slab once its operands have arrived (the workgroup barrier and what follows it)."""
     anchors = []
     for s in range(8):
         for n, (kb, qg) in enumerate(((0, 0), (0, 1), (1, 0), (1, 1))):
@@ -236,16 +239,19 @@ def qk_anchors(ty, koff, with_dma):
                 if s + 2 < 8:
                     before += k_reads(s + 2, koff)
                 before.append(f"s_waitcnt lgkmcnt({2 * min(2, 7 - s)})")
+                if s == 7:
+                    before += list(sync)
             c = "0" if s == 0 else St(ty, kb, qg)
             mfma = f"v_mfma_f32_32x32x16_bf16 {St(ty, kb, qg)}, {Ka(s % 3, kb)}, {Qt(s, qg)}, {c}"
-            if with_dma and n == 1:
-                after += dma(s)
             anchors.append((before, mfma, after))
+    for d, a in enumerate(dma_at):
+        anchors[a][2].extend(dma_pair(d))
     return anchors
 
 
-def pv_anchors(tx, voff, slabs, dma_at=()):
-    """16-key slabs of O^T += V^T P_tx; operands of slab j+1 are read while slab j multiplies."""
+def pv_anchors(tx, voff, slabs, dma_at=(), sync=(), first_read=True):
+    """16-key slabs of O^T += V^T P_tx; operands of slab j+1 are read while slab j multiplies.
+    sync: as in qk_anchors, in front of slab 3."""
     anchors = []
     for j in slabs:
         st = j & 1
@@ -257,12 +263,15 @@ def pv_anchors(tx, voff, slabs, dma_at=()):
                     before.append("s_waitcnt lgkmcnt(8)")
                 else:
                     before.append("s_waitcnt lgkmcnt(0)")
+                    before += list(sync)
             mfma = f"v_mfma_f32_32x32x16_bf16 {Ot(db, qg)}, {Vt(st, db)}, {Pt(tx, j, qg)}, {Ot(db, qg)}"
             anchors.append((before, mfma, after))
     for d, a in enumerate(dma_at):
-        anchors[a][2].extend(dma(d))
+        anchors[a][2].extend(dma_pair(d))
     return anchors
 
+
+SYNC = ["s_waitcnt vmcnt(16)", "s_barrier"]  # all but the two youngest sub-tile loads have landed, in both waves
 
 ALL_CLOBBERS = ", ".join([f'"v{i}"' for i in range(64, 256)] + [f'"a{i}"' for i in range(8, 256)])
 
@@ -377,19 +386,26 @@ def main():
                            lambda t, prs=prs: emit(flat(*softmax_groups(t, prs)), SM_OUT, SM_IN)))
 
     # ---- S_0 = K_0 Q^T (first sub-tile, K buffer 0)
-    lines = k_reads(0, 0) + k_reads(1, 0) + weave(qk_anchors(0, 0, False), [], [], []) + ["s_nop 15"]
+    lines = k_reads(0, 0) + k_reads(1, 0) + weave(qk_anchors(0, 0), [], [], []) + ["s_nop 15"]
     ka_in = ", ".join(f'[ka{s}] "v"(ka[{s}])' for s in range(8))
     o.append("__device__ __forceinline__ void pipe_qk_first(const uint32_t (&ka)[8]) {\n" + emit(lines, "", ka_in) + "}\n\n")
 
-    # ---- phase A(i), PAR = i & 1: S_{i+1} = K_{i+1} Q^T | softmax of pairs PAIRS_A of sub-tile i | DMA of V_{i+1}
+    va_in = ", ".join(f'[va{d}] "v"(va[{d}])' for d in range(4))
+
+    # ---- K operand reads of the first two k-slabs of K buffer KBUF (before the first phase A; later ones
+    #      are issued by the phase B2 in front)
+    o.append(by_index("KBUF", 2, "pipe_k_preread(const uint32_t (&ka)[8])", "",
+                      lambda kbuf: emit(k_reads(0, kbuf * 16384) + k_reads(1, kbuf * 16384), "", '[ka0] "v"(ka[0]), [ka1] "v"(ka[1])')))
+
+    # ---- phase A(i), PAR = i & 1: S_{i+1} = K_{i+1} Q^T | softmax of pairs PAIRS_A of sub-tile i | DMA of V_{i+1}.
+    #      In front of the last k-slab: barrier (V_i has landed, K_{i+1} is read) and the first V operand reads.
     def phase_a(par):
         x, y = par, 1 - par
         koff = (1 - par) * 16384
-        lines = k_reads(0, koff) + k_reads(1, koff) + weave(qk_anchors(y, koff, True), *softmax_groups(x, PAIRS_A))
-        return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{ka_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"', tag="a")
-    o.append(by_parity(f"pipe_phase_a(const uint32_t (&ka)[8], {SM_SIG}, {DMA_SIG})", T6_DECL + "  uint32_t st;\n", phase_a))
-
-    va_in = ", ".join(f'[va{d}] "v"(va[{d}])' for d in range(4))
+        sync = SYNC + v_reads(0, 0, par * 16384)
+        lines = weave(qk_anchors(y, koff, (1, 9, 17, 25), sync), *softmax_groups(x, PAIRS_A))
+        return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{ka_in}, {va_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"', tag="a")
+    o.append(by_parity(f"pipe_phase_a(const uint32_t (&ka)[8], const uint32_t (&va)[4], {SM_SIG}, {DMA_SIG})", T6_DECL + "  uint32_t st;\n", phase_a))
 
     # ---- phase B1(i): slabs 0-1 of O += V_i^T P_i | softmax of pairs PAIRS_B1 of sub-tile i | row maxima of S_{i+1}
     def phase_b1(par):
@@ -397,17 +413,20 @@ def main():
         voff = par * 16384
         pre, groups, tail = softmax_groups(x, PAIRS_B1)
         mx = max_ops(y)
-        lines = v_reads(0, 0, voff) + weave(pv_anchors(x, voff, (0, 1)), pre + mx[:8], groups, tail, mx[8:] + combine_ops())
+        lines = weave(pv_anchors(x, voff, (0, 1)), pre, groups, tail, mx + combine_ops())
         return emit(lines, f"{SM_OUT}, {MX_OUT}", f"{va_in}, {SM_IN}, [sy] \"v\"(sy)", tag="b1")
     o.append(by_parity(f"pipe_phase_b1(const uint32_t (&va)[4], {SM_SIG}, float sy, float (&mx)[2])", T6_DECL + MX_DECL, phase_b1))
 
-    # ---- phase B2(i): slabs 2-3 | softmax of pairs PAIRS_B2 of sub-tile i+1 | DMA of K_{i+3}
+    # ---- phase B2(i): slabs 2-3 | softmax of pairs PAIRS_B2 of sub-tile i+1 | DMA of K_{i+3}.
+    #      In front of the last slab: barrier (K_{i+2} has landed, V_i is read) and the K operand reads of
+    #      the first two k-slabs of the next phase A.
     def phase_b2(par):
         x, y = par, 1 - par
         voff = par * 16384
-        lines = weave(pv_anchors(x, voff, (2, 3), (1, 3, 5, 7, 9, 11, 13, 15)), *softmax_groups(y, PAIRS_B2))
-        return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{va_in}, {SM_IN}, {DMA_IN}", ', "m0", "scc"', tag="b2")
-    o.append(by_parity(f"pipe_phase_b2(const uint32_t (&va)[4], {SM_SIG}, {DMA_SIG})", T6_DECL + "  uint32_t st;\n", phase_b2))
+        sync = SYNC + k_reads(0, par * 16384) + k_reads(1, par * 16384)
+        lines = weave(pv_anchors(x, voff, (2, 3), (1, 3, 5, 7), sync), *softmax_groups(y, PAIRS_B2))
+        return emit(lines, f"{SM_OUT}, {DMA_OUT}", f"{va_in}, [ka0] \"v\"(ka[0]), [ka1] \"v\"(ka[1]), {SM_IN}, {DMA_IN}", ', "m0", "scc"', tag="b2")
+    o.append(by_parity(f"pipe_phase_b2(const uint32_t (&va)[4], const uint32_t (&ka)[8], {SM_SIG}, {DMA_SIG})", T6_DECL + "  uint32_t st;\n", phase_b2))
 
     # ---- O += V_i^T P_i without a partner (last sub-tile)
     def pv_plain(par):
