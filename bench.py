@@ -23,6 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6  # 256 CUs x 4096 FLOP/clk/CU x 2.4 GHz (published 2.5 PFLOP/s dense bf16)
+NOMINAL_MHZ = 2400.0
 
 
 def parse_args():
@@ -169,6 +170,16 @@ def main():
         dense = {"ms": d_ev, "tflops": hd.nnz * wl.B * tile_flops / (d_ev * 1e-3) / 1e12,
                  "speedup_sparse_vs_dense": d_ev / ev_mean_ms}
 
+    # clock the GPU sustained during the last timed launch (diagnostic words of the workspace)
+    observed = None
+    if getattr(dp, "counter", None) is not None:
+        words = dp.counter.cpu().tolist()
+        if words[10] > 0 and words[11] > 0:
+            mhz = 100.0 * words[10] / words[11]
+            peak_at_clock = PEAK_BF16_TFLOPS * mhz / NOMINAL_MHZ
+            observed = {"sclk_mhz": mhz, "mfma_peak_at_that_clock_tflops": peak_at_clock,
+                        "frac_of_peak_at_that_clock": achieved / peak_at_clock}
+
     result = {
         "metric": "computed-block bf16 TFLOP/s (% MFMA peak); speedup vs dense @ Wan 480p shape",
         "value": value,
@@ -196,6 +207,8 @@ def main():
         "kernel_ms_mean": ev_mean_ms,
         "kernel_ms_median": ev_med_ms,
         "dense_reference": dense,
+        "observed_clock": observed,
+        "kernel_variant": os.environ.get("CALIBATT_KERNEL", "2wg"),
         "roofline": {
             "bound": "mfma",
             "achieved": achieved,

@@ -141,8 +141,13 @@ int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repeat, int H, 
  *                  CALIBATT_GROUPS a workgroup first drains the group of the
  *                  XCD it runs on - the heads of one group then share that
  *                  XCD's L2 - and steals from the other groups afterwards.
- *                  The last workgroup to finish sets all words back to zero,
+ *                  The last workgroup to finish sets words 0..8 back to zero,
  *                  so consecutive calls on one stream may share the workspace.
+ *                  Words 10 and 11 hold a diagnostic after every launch:
+ *                  shader-clock cycles and ticks of the constant 100 MHz
+ *                  counter during which workgroup 0 was resident (ratio x 100
+ *                  MHz = the clock the GPU sustained); the other words are
+ *                  reserved.
  *                  Calls that overlap in time (different streams) need
  *                  separate workspaces.  calibatt_compile_pattern sets NULL.
  * scale    multiplies the logits before the softmax (1/sqrt(D) in Eq. 1).

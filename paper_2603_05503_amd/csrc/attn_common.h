@@ -71,11 +71,6 @@ __device__ __forceinline__ u32x4 head_rsrc(const uint16_t *base, uint32_t bytes)
 // in-flight vector-memory operation (it would otherwise drain vmcnt before
 // every LDS read); completion is tracked by hand with wait_vmem<>().
 __device__ __forceinline__ void dma_16B_per_lane(const u32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_off) {
-#ifdef CALIBATT_DEBUG_BUILTIN_DMA
-  __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)rsrc[1] << 32) | rsrc[0]), 0, rsrc[2], 0x00020000);
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rr, (LDS_PTR(void))(uintptr_t)lds_off, 16, voff, soff, 0, 0);
-  return;
-#endif
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
       "s_nop 0\n\t"  // one wait state between the M0 write and the LDS-DMA that reads it
@@ -112,6 +107,21 @@ struct TileLoader {
       const uint32_t soff = (uint32_t)(row0 + it * RPI) * (D * 2);
       dma_16B_per_lane(rsrc, voff, soff, lds_wave_off + it * NT * 16);
     }
+  }
+};
+
+// Diagnostic kept in the caller's workspace: how long workgroup 0 was resident, in shader-clock
+// cycles (word 10) and in ticks of the constant 100 MHz counter (word 11).  Their ratio is the
+// clock the GPU sustained during the launch.
+struct ResidencyClock {
+  uint64_t cycles0, ticks0;
+  __device__ __forceinline__ void start() {
+    cycles0 = __builtin_amdgcn_s_memtime();
+    ticks0 = __builtin_amdgcn_s_memrealtime();
+  }
+  __device__ __forceinline__ void store(int32_t *workspace) const {
+    workspace[10] = (int32_t)(__builtin_amdgcn_s_memtime() - cycles0);
+    workspace[11] = (int32_t)(__builtin_amdgcn_s_memrealtime() - ticks0);
   }
 };
 

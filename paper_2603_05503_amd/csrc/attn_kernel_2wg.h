@@ -80,13 +80,11 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   // on the group of the XCD it runs on (the heads of a group then share that
   // XCD's L2) and moves on to the next group, for good, once one is empty.
   // Otherwise: one workgroup per pair.
-#ifdef CALIBATT_DEBUG_TIMING
-  const long long dbg_t0 = wall_clock64();
-  int dbg_items = 0, dbg_tiles = 0;
-#endif
   int cur_group = 0, groups_left = p.n_groups;
   if (counter && p.n_groups > 1)
     cur_group = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) % p.n_groups;  // HW_REG_XCC_ID[3:0]
+  ResidencyClock residency;
+  residency.start();
   for (int wg_item = blockIdx.x;;) {
   if (counter) {
     if (tid == 0) {
@@ -110,10 +108,6 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   const int item = wg_item / p.B;
   const int b = wg_item - item * p.B;
   const int id = work[item];
-#ifdef CALIBATT_DEBUG_TIMING
-  ++dbg_items;
-  dbg_tiles += row_ptr[id + 1] - row_ptr[id];
-#endif
   const int h = id / p.nbq;
   const int r = id - h * p.nbq;
   const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
@@ -261,12 +255,8 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-#ifdef CALIBATT_DEBUG_NO_EXP
-        const float p0 = s_acc[kb][v], p1 = s_acc[kb][v + 1];
-#else
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v], sc_t, -m_new));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v + 1], sc_t, -m_new));
-#endif
         const uint32_t pk = pack_bf16(p0, p1);
         pb[kb][v >> 1] = pk;
         psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, psum, false);
@@ -355,16 +345,8 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   __syncthreads();  // staging tile fully read before the next item's loads overwrite it
   }  // work-item loop
 
-#ifdef CALIBATT_DEBUG_TIMING
-  if (counter && tid == 0) {
-    long long *dbg = reinterpret_cast<long long *>(counter + 32) + 4 * blockIdx.x;
-    dbg[0] = dbg_t0;
-    dbg[1] = wall_clock64();
-    dbg[2] = dbg_items;
-    dbg[3] = dbg_tiles | ((long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) << 32);
-  }
-#endif
-  // Last workgroup out re-arms the counter pair for the next launch.
+  if (counter && blockIdx.x == 0 && tid == 0) residency.store(counter);
+  // Last workgroup out re-arms the counters for the next launch.
   if (counter && tid == 0) {
     __threadfence();
     if (atomicAdd(counter + CALIBATT_GROUPS, 1) == (int)gridDim.x - 1) {

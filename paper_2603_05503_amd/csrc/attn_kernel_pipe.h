@@ -71,9 +71,7 @@ struct PipeLds {
 };
 
 __device__ __forceinline__ void pipe_barrier() {
-#ifndef PIPE_DEBUG_NO_BARRIER
   asm volatile("s_barrier");
-#endif
 }
 
 template <int D, int BQ, int BK>
@@ -144,6 +142,8 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
   int cur_group = 0, groups_left = p.n_groups;
   if (counter && p.n_groups > 1)
     cur_group = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) % p.n_groups;  // HW_REG_XCC_ID[3:0]
+  ResidencyClock residency;
+  residency.start();
 
   for (int wg_item = blockIdx.x;;) {
     if (counter) {
@@ -349,6 +349,7 @@ __global__ __launch_bounds__(PIPE_THREADS, 1) __attribute__((amdgpu_num_vgpr(64)
     __syncthreads();  // staging tile fully read before the next item's loads overwrite it
   }
 
+  if (counter && blockIdx.x == 0 && tid == 0) residency.store(counter);
   if (counter && tid == 0) {
     __threadfence();
     if (atomicAdd(counter + CALIBATT_GROUPS, 1) == (int)gridDim.x - 1) {

@@ -18,3 +18,12 @@ def lib():
     import paper_2603_05503_amd as pkg
 
     return pkg
+
+
+@pytest.fixture(params=["2wg", "pipe"])
+def kernel_variant(request, monkeypatch):
+    """Runs a GPU test once per kernel: the library reads CALIBATT_KERNEL on every call; "pipe"
+    selects the in-wave pipelined kernel for 128 x 128 x 128 blocks (other shapes take the
+    two-workgroup kernel either way)."""
+    monkeypatch.setenv("CALIBATT_KERNEL", request.param)
+    return request.param

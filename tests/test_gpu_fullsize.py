@@ -9,7 +9,7 @@ from oracle import sparse_attention_blocks
 from tests.parity_utils import MAX_ABS, MEAN_ABS, assert_repeats_bitwise, bits_to_f64, from_dev, to_dev
 from workloads import make_workload
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("kernel_variant")]
 
 
 def _sample_items(wl, rng, per_stratum=6):
@@ -49,6 +49,12 @@ def test_fullsize_sampled_parity(lib, name, density):
     lib.sparse_attn_fwd(q, k, v, out2, dp, wl.scale)
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "run-to-run difference"
+    # more work items than resident workgroups: the persistent path ran, re-armed its counters and
+    # left the residency diagnostic of workgroup 0 (shader cycles, 100 MHz ticks)
+    words = dp.counter.cpu().tolist()
+    assert words[:9] == [0] * 9
+    cycles, ticks = words[10], words[11]
+    assert cycles > 0 and ticks > 0 and 300 < 100.0 * cycles / ticks < 3000, (cycles, ticks)
     assert_repeats_bitwise(got, wl.repeat, wl.block_q, wl.N)
 
     rng = np.random.default_rng(99)

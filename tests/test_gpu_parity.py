@@ -9,7 +9,7 @@ from oracle import sparse_attention
 from tests.parity_utils import assert_parity, assert_repeats_bitwise, error_stats, run_gpu
 from workloads import f32_to_bf16_bits, make_workload, random_mask
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("kernel_variant")]
 
 
 def _qkv(seed, B, H, N, D, gain=1.0):

@@ -9,7 +9,7 @@ from oracle import sparse_attention
 from tests.parity_utils import assert_parity, assert_repeats_bitwise, bits_to_f64, from_dev, run_gpu, to_dev
 from workloads import f32_to_bf16_bits, random_mask
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("kernel_variant")]
 
 
 def _qkv(seed, B, H, N, D, gain=1.0):
@@ -108,13 +108,16 @@ def test_run_to_run_bitwise_and_scheduler_independent(lib, persistent):
                 ref = bits
             assert (bits == ref).all(), order
         if persistent:
-            assert dp.counter.cpu().tolist() == [0] * 16
+            words = dp.counter.cpu().tolist()
+            assert words[:9] == [0] * 9  # counters re-armed by the last workgroup
+            assert words[12:] == [0] * 4  # reserved words untouched
     assert_repeats_bitwise(ref, repeat, blk, N)
 
 
-def test_negative_and_zero_scale(lib):
-    print("scale sign", flush=True)
-    B, H, N, D, blk = 1, 1, 300, 64, 64
+@pytest.mark.parametrize("D,blk,N", [(64, 64, 300), (128, 128, 600)])
+def test_negative_and_zero_scale(lib, D, blk, N):
+    print(f"scale sign D={D} blk={blk}", flush=True)
+    B, H = 1, 1
     q, k, v = _qkv(13, B, H, N, D, 2.0)
     nb = -(-N // blk)
     mask, _ = random_mask(14, H, nb, nb, 0.7, keep_diagonal=True)
