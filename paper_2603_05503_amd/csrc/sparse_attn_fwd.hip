@@ -8,6 +8,7 @@
 
 #include "attn_kernel_2wg.h"
 #include "attn_kernel_pipe.h"
+#include "attn_kernel_pp.h"
 #include "calibatt.h"
 
 namespace {
@@ -55,12 +56,15 @@ int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, c
   return hipGetLastError() == hipSuccess ? CALIBATT_OK : CALIBATT_ERR_LAUNCH;
 }
 
-// CALIBATT_KERNEL=pipe in the environment selects the in-wave pipelined kernel where its
-// shape is covered; anything else the two-workgroups-per-CU kernel.  Both compute the same
-// thing; measured throughput on MI355X is the same within run-to-run noise.  Read per call.
-bool pipelined_wanted() {
+// CALIBATT_KERNEL in the environment selects the kernel where its shape is covered: "pp" the
+// ping-pong kernel (two wavefront groups per workgroup), "pipe" the in-wave pipelined one,
+// anything else the two-workgroups-per-CU kernel.  All compute the same thing.  Read per call.
+enum class Variant { TwoWg, Pipe, PingPong };
+Variant wanted_variant() {
   const char *e = std::getenv("CALIBATT_KERNEL");
-  return e && std::strcmp(e, "pipe") == 0;
+  if (e && std::strcmp(e, "pipe") == 0) return Variant::Pipe;
+  if (e && std::strcmp(e, "pp") == 0) return Variant::PingPong;
+  return Variant::TwoWg;
 }
 
 template <int D, int BQ, int BK>
@@ -69,8 +73,18 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
   if (items <= 0) return CALIBATT_OK;
   if (items > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
   int slots = 0;
+  const Variant variant = wanted_variant();
+  if constexpr (BQ <= BK) {
+    if (variant == Variant::PingPong) {
+      static DevInfo info[64];
+      constexpr int SMEM = PpLds<D, BQ, BK>::BYTES;
+      auto kernel = sparse_attn_fwd_pp_kernel<D, BQ, BK>;
+      if (int st = prepare(kernel, BQ * 4, SMEM, info, slots)) return st;
+      return enqueue(kernel, BQ * 4, SMEM, slots, a, p, stream);
+    }
+  }
   if constexpr (D == 128 && BQ == 128 && BK == 128) {
-    if (max_row <= PIPE_COL_CAP && pipelined_wanted()) {
+    if (max_row <= PIPE_COL_CAP && variant == Variant::Pipe) {
       static DevInfo info[64];
       constexpr int SMEM = PipeLds<D, BQ, BK>::BYTES;
       auto kernel = sparse_attn_fwd_pipe_kernel<D, BQ, BK>;
