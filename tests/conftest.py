@@ -20,10 +20,11 @@ def lib():
     return pkg
 
 
-@pytest.fixture(params=["2wg", "pipe"])
+@pytest.fixture(params=["2wg", "pipe", "pp"])
 def kernel_variant(request, monkeypatch):
-    """Runs a GPU test once per kernel: the library reads CALIBATT_KERNEL on every call; "pipe"
-    selects the in-wave pipelined kernel for 128 x 128 x 128 blocks (other shapes take the
-    two-workgroup kernel either way)."""
+    """Runs a GPU test once per kernel: the library reads CALIBATT_KERNEL on every call.  "pipe"
+    selects the in-wave pipelined kernel for 128 x 128 x 128 blocks, "pp" the ping-pong kernel for
+    shapes with block_q <= block_k; shapes a variant does not cover take the default
+    two-workgroup kernel."""
     monkeypatch.setenv("CALIBATT_KERNEL", request.param)
     return request.param
