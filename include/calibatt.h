@@ -11,6 +11,8 @@
  *   2. at every attention call: calibatt_sparse_attn_fwd() runs the tiled
  *      forward (Section 2, Eq. 3-4: per query block, loop over key/value
  *      blocks with an online softmax) over the kept blocks only.
+ * Heads flagged as spatially repetitive (Section 3.3 at token-row granularity)
+ * go through calibatt_anchor_map() / calibatt_anchor_attn_fwd() instead.
  *
  * Plain C, no exceptions cross the boundary, no global state is kept between
  * calls, every buffer is owned by the caller.  All functions return a
@@ -160,6 +162,66 @@ int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repeat, int H, 
 int calibatt_sparse_attn_fwd(const void *q, const void *k, const void *v, void *out, int B, int H,
                              int N, int D, int block_q, int block_k,
                              const calibatt_pattern *pattern, float scale, void *stream);
+
+/*
+ * Spatial-row anchor scheme (Section 3.3; "Inference stage" of Section 3.4:
+ * heads flagged as spatially repetitive run dense attention on a reduced query
+ * set and broadcast the result).
+ *
+ * Geometry: the first F*Hs*Ws tokens of a head are a video latent, token
+ * (frame f, spatial row y, column x) at index (f*Hs + y)*Ws + x; the remaining
+ * N - F*Hs*Ws tokens (text tokens of joint-attention models) have no position.
+ * Per frame, k anchor rows a_j = floor((2j+1)*Hs / (2k)), j = 0..k-1 (the rows
+ * under the centres of k equal segments).  Row y takes the result of the
+ * anchor nearest to it, the lower one on a tie.  Tokens without a position are
+ * computed themselves.
+ *
+ * calibatt_anchor_map writes, into caller-provided HOST buffers,
+ *   q_index [n_q]      token whose query is the i-th computed one: frames
+ *                      ascending, then anchors ascending, then columns; then
+ *                      the tokens without a position
+ *   dst_ptr [n_q + 1]  exclusive prefix sum of the receiver counts
+ *   dst_idx [N]        receivers of computed query i: dst_idx[dst_ptr[i] ..
+ *                      dst_ptr[i+1]), ascending; every token is listed once
+ *   *n_q               F*k*Ws + (N - F*Hs*Ws)
+ * Any of the three arrays may be NULL (then none is written): use that to
+ * learn n_q.  Errors: NULL (n_q), SHAPE (a non-positive dimension, F*Hs*Ws > N,
+ * k > Hs).
+ */
+int calibatt_anchor_map(int N, int F, int Hs, int Ws, int k, int32_t *q_index, int32_t *dst_ptr,
+                        int32_t *dst_idx, int32_t *n_q);
+
+/*
+ * Dense attention on a reduced query set with broadcast of the results
+ * (Section 3.3; Section 2, Eq. 1-4 for the attention itself).
+ *
+ * q, k, v  DEVICE, bf16, contiguous [B][H][N][D]; read only.
+ * out      DEVICE, bf16, contiguous [B][H][N][D]; must not alias the inputs.
+ *          Only the heads listed in head_ids are touched.  In those, for every
+ *          i < n_q, softmax(scale * q[q_index[i]] K^T) V over all N keys (fp32
+ *          accumulation, rounded to bf16) is written to each row
+ *          dst_idx[dst_ptr[i] .. dst_ptr[i+1]); all receivers of one i hold
+ *          the same bits.  Rows that no list names keep their contents.
+ * head_ids DEVICE int32 [n_heads]: the heads to process, each in [0, H); an
+ *          entry outside that range is skipped.  The other heads of `out` are
+ *          left to calibatt_sparse_attn_fwd (give these heads an empty mask
+ *          there and enqueue this call after it on the same stream, or run the
+ *          two on disjoint tensors).
+ * q_index, dst_ptr, dst_idx  DEVICE copies of what calibatt_anchor_map wrote,
+ *          or any other lists of that form (q_index entries are clamped to
+ *          [0, N), dst_idx entries outside [0, N) are skipped; dst_ptr must be
+ *          non-decreasing with dst_ptr[0] >= 0 and is not checked).  The same
+ *          lists serve every listed head and every batch index.
+ * stream   hipStream_t (NULL = default stream).  The call only enqueues work.
+ *
+ * Supported: D in {64, 128}.  n_heads == 0 or n_q == 0 is a no-op.
+ * Errors: NULL, SHAPE (non-positive B/H/N/D, negative n_heads or n_q, out
+ * aliasing an input), UNSUPPORTED (D), LAUNCH.
+ */
+int calibatt_anchor_attn_fwd(const void *q, const void *k, const void *v, void *out, int B, int H,
+                             int N, int D, const int32_t *head_ids, int n_heads,
+                             const int32_t *q_index, const int32_t *dst_ptr, const int32_t *dst_idx,
+                             int n_q, float scale, void *stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char *calibatt_strerror(int status);

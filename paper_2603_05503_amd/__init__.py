@@ -6,8 +6,12 @@ library has not been built, loading fails with an error.
 """
 from .binding import (  # noqa: F401
     CalibattError,
+    DeviceAnchorMap,
     DevicePattern,
+    HostAnchorMap,
     HostPattern,
+    anchor_attn_fwd,
+    anchor_map,
     compile_pattern,
     library_path,
     load_library,

@@ -48,6 +48,12 @@ def load_library():
             f"{_LIB_PATH} is missing: build it with `python -m paper_2603_05503_amd.build` "
             "(there is no fallback path)"
         )
+    # Device pointers and streams handed to the library come from torch, so both must sit on ONE HIP
+    # runtime.  torch ships its own copy; loading torch first makes the dynamic linker resolve the
+    # library's libamdhip64 dependency to that already loaded copy instead of a second runtime
+    # (which would not see torch's device context).
+    import torch  # noqa: F401
+
     lib = C.CDLL(_LIB_PATH)
     i32p, u8p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.POINTER(C.c_int64)
     lib.calibatt_pattern_sizes.restype = C.c_int
@@ -62,6 +68,15 @@ def load_library():
         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
         C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
         C.POINTER(_CPattern), C.c_float, C.c_void_p,
+    ]
+    lib.calibatt_anchor_map.restype = C.c_int
+    lib.calibatt_anchor_map.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p]
+    lib.calibatt_anchor_attn_fwd.restype = C.c_int
+    lib.calibatt_anchor_attn_fwd.argtypes = [
+        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+        C.c_int, C.c_int, C.c_int, C.c_int,
+        C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+        C.c_float, C.c_void_p,
     ]
     lib.calibatt_strerror.restype = C.c_char_p
     lib.calibatt_strerror.argtypes = [C.c_int]
@@ -223,4 +238,71 @@ def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
                                       B, H, N, D, bq, bk, C.byref(pattern.c), float(scale), C.c_void_p(stream))
     if st != 0:
         raise CalibattError(st, "calibatt_sparse_attn_fwd")
+    return out
+
+
+@dataclass
+class HostAnchorMap:
+    """Output of calibatt_anchor_map in host (NumPy) buffers."""
+    N: int
+    n_q: int
+    q_index: np.ndarray
+    dst_ptr: np.ndarray
+    dst_idx: np.ndarray
+
+    def to_device(self, device="cuda") -> "DeviceAnchorMap":
+        return DeviceAnchorMap(self, device)
+
+
+def anchor_map(N, F, Hs, Ws, k) -> HostAnchorMap:
+    lib = load_library()
+    n_q = C.c_int32(0)
+    st = lib.calibatt_anchor_map(N, F, Hs, Ws, k, None, None, None, C.byref(n_q))
+    if st != 0:
+        raise CalibattError(st, "calibatt_anchor_map")
+    q_index = np.empty(n_q.value, np.int32)
+    dst_ptr = np.empty(n_q.value + 1, np.int32)
+    dst_idx = np.empty(N, np.int32)
+    st = lib.calibatt_anchor_map(N, F, Hs, Ws, k, _ptr(q_index, C.c_int32), _ptr(dst_ptr, C.c_int32),
+                                 _ptr(dst_idx, C.c_int32), C.byref(n_q))
+    if st != 0:
+        raise CalibattError(st, "calibatt_anchor_map")
+    return HostAnchorMap(N=N, n_q=int(n_q.value), q_index=q_index, dst_ptr=dst_ptr, dst_idx=dst_idx)
+
+
+class DeviceAnchorMap:
+    """The three lists of an anchor map as int32 torch tensors on the GPU."""
+
+    def __init__(self, hm: HostAnchorMap, device="cuda"):
+        import torch
+
+        self.host = hm
+        self.n_q = hm.n_q
+        self.q_index = torch.from_numpy(np.ascontiguousarray(hm.q_index, dtype=np.int32)).to(device)
+        self.dst_ptr = torch.from_numpy(np.ascontiguousarray(hm.dst_ptr, dtype=np.int32)).to(device)
+        self.dst_idx = torch.from_numpy(np.ascontiguousarray(hm.dst_idx, dtype=np.int32)).to(device)
+
+
+def anchor_attn_fwd(q, k, v, out, head_ids, amap: DeviceAnchorMap, scale: float, stream=None):
+    """calibatt_anchor_attn_fwd on torch bf16 CUDA tensors [B, H, N, D];
+    ``head_ids`` is an int32 CUDA tensor of the heads to process."""
+    import torch
+
+    lib = load_library()
+    for t in (q, k, v, out):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
+            raise ValueError("q, k, v, out must be contiguous bf16 CUDA tensors [B, H, N, D]")
+        if t.shape != q.shape:
+            raise ValueError("q, k, v, out must have the same shape")
+    if not (head_ids.is_cuda and head_ids.dtype == torch.int32 and head_ids.is_contiguous() and head_ids.dim() == 1):
+        raise ValueError("head_ids must be a contiguous 1-d int32 CUDA tensor")
+    B, H, N, D = q.shape
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = lib.calibatt_anchor_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, D,
+                                      head_ids.data_ptr(), head_ids.numel(), amap.q_index.data_ptr(),
+                                      amap.dst_ptr.data_ptr(), amap.dst_idx.data_ptr(), amap.n_q,
+                                      float(scale), C.c_void_p(stream))
+    if st != 0:
+        raise CalibattError(st, "calibatt_anchor_attn_fwd")
     return out

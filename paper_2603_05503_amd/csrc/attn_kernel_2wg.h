@@ -34,149 +34,93 @@
 
 namespace calibatt_dev {
 
+// One workgroup's share of the forward: BQ query rows against a sequence of
+// BK-key tiles.  Holds the per-lane state (Q^T operand, O^T accumulators,
+// running max / sum) and the LDS addressing; the kernels decide which rows,
+// which tiles, and where the result goes.
 template <int D, int BQ, int BK>
-__global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_kernel(
-    const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
-    uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
-    int32_t *counter, const FwdDims p) {
-  constexpr int NW = BQ / 32;     // wavefronts per workgroup
-  constexpr int NT = NW * 64;     // threads
-  constexpr int CH = D / 8;       // 16-byte chunks per row
-  constexpr int KB = BK / 32;     // 32-key sub-blocks per tile
-  constexpr int DS = D / 16;      // k-slabs of the QK^T contraction
-  constexpr int DB = D / 32;      // 32-wide d blocks of O^T
-  constexpr int ROWB = D * 2;     // bytes per LDS row
-  constexpr int TILE_BYTES = BK * ROWB;
-  constexpr int OST = ROWB + 16;  // padded row stride of the output staging tile
-  constexpr int LDS_BYTES = (2 * TILE_BYTES > BQ * OST) ? 2 * TILE_BYTES : BQ * OST;
+struct RowBlock {
+  static constexpr int NW = BQ / 32;     // wavefronts per workgroup
+  static constexpr int NT = NW * 64;     // threads
+  static constexpr int CH = D / 8;       // 16-byte chunks per row
+  static constexpr int KB = BK / 32;     // 32-key sub-blocks per tile
+  static constexpr int DS = D / 16;      // k-slabs of the QK^T contraction
+  static constexpr int DB = D / 32;      // 32-wide d blocks of O^T
+  static constexpr int ROWB = D * 2;     // bytes per LDS row
+  static constexpr int TILE_BYTES = BK * ROWB;
+  static constexpr int OST = ROWB + 16;  // padded row stride of the output staging tile
+  static constexpr int LDS_BYTES = (2 * TILE_BYTES > BQ * OST) ? 2 * TILE_BYTES : BQ * OST;
   using LoadK = TileLoader<D, BK, NT, false>;
   using LoadV = TileLoader<D, BK, NT, true>;
-  constexpr int LOADS_PER_WAVE = LoadK::ITERS;  // direct-to-LDS instructions per wave and tile
+  static constexpr int LOADS_PER_WAVE = LoadK::ITERS;  // direct-to-LDS instructions per wave and tile
 
-  extern __shared__ __attribute__((aligned(1024))) char lds[];  // LDS_BYTES + 64 (work-item mailbox)
-  char *const ldsK = lds;
-  char *const ldsV = lds + TILE_BYTES;
+  char *lds, *ldsK, *ldsV;
+  int tid, lane, wave, l32, g;
+  uint32_t k_lane_off, v_lane_off, ldsK_wave, ldsV_wave;
+  uint32_t k_addr0, v_addr[DB];
+  bf16x8 qreg[DS];  // Q^T as MFMA B operand: lane (query l32, half g) holds d = 16 s + 8 g + [0,8)
+  f32x16 o[DB];
+  float m_run;  // running max of scaled (log2-domain) logits, shared by lane and lane^32
+  float l_run;  // this lane's share of the running row sum
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int l32 = lane & 31;
-  const int g = lane >> 5;
-
-  const uint32_t k_lane_off = LoadK::lane_offset(tid, 0);
-  const uint32_t v_lane_off = LoadV::lane_offset(tid, 0);
-  const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
-  const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const uint32_t ldsK_wave = lds_base + wave_u * 1024;
-  const uint32_t ldsV_wave = ldsK_wave + TILE_BYTES;
-  const int N = p.N;
-  const int n_items = p.n_work * p.B;
-  volatile int *const mailbox = reinterpret_cast<volatile int *>(lds + LDS_BYTES);
-
-  // Persistent workgroups (counter != nullptr): every workgroup pops (work item,
-  // batch index) pairs from per-group counters until all groups are drained, so
-  // uneven rows balance dynamically.  With one group per XCD a workgroup starts
-  // on the group of the XCD it runs on (the heads of a group then share that
-  // XCD's L2) and moves on to the next group, for good, once one is empty.
-  // Otherwise: one workgroup per pair.
-  int cur_group = 0, groups_left = p.n_groups;
-  if (counter && p.n_groups > 1)
-    cur_group = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) % p.n_groups;  // HW_REG_XCC_ID[3:0]
-  ResidencyClock residency;
-  residency.start();
-  for (int wg_item = blockIdx.x;;) {
-  if (counter) {
-    if (tid == 0) {
-      int found = -1;
-      while (groups_left > 0) {
-        const int it = atomicAdd(counter + cur_group, 1);
-        if (it < (p.group_ptr[cur_group + 1] - p.group_ptr[cur_group]) * p.B) {
-          found = p.group_ptr[cur_group] * p.B + it;
-          break;
-        }
-        cur_group = cur_group + 1 == p.n_groups ? 0 : cur_group + 1;
-        --groups_left;
-      }
-      *mailbox = found;
-    }
-    __syncthreads();
-    wg_item = __builtin_amdgcn_readfirstlane(*mailbox);
-    if (wg_item < 0) break;
+  __device__ __forceinline__ explicit RowBlock(char *lds_) : lds(lds_), ldsK(lds_), ldsV(lds_ + TILE_BYTES) {
+    tid = threadIdx.x;
+    lane = tid & 63;
+    wave = tid >> 6;
+    l32 = lane & 31;
+    g = lane >> 5;
+    k_lane_off = LoadK::lane_offset(tid, 0);
+    v_lane_off = LoadV::lane_offset(tid, 0);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    ldsK_wave = lds_base + wave_u * 1024;
+    ldsV_wave = ldsK_wave + TILE_BYTES;
+    // K operand row for MFMA row i = l32: swap bits 2 and 3 so that the 8 S^T
+    // values a lane holds per 16-key slab belong to 8 consecutive keys.  With the
+    // XOR swizzle the address of k-slab s is k_addr0 ^ (s << 5).
+    const int krow_in_kb = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+    k_addr0 = krow_in_kb * ROWB + ((g ^ k_swz<D>(krow_in_kb)) << 4);
+    // transposing V read: 16-lane block -> (d sub-block, key half); lane L16 in block
+    const int L16 = lane & 15;
+    const int blk = lane >> 4;
+    const int v_row_off = 8 * (blk >> 1) + (L16 >> 2);  // + 32 kb + 16 s2 + 4 t
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      v_addr[db] = v_row_off * ROWB + (((4 * db + 2 * (blk & 1) + ((L16 & 3) >> 1)) ^ v_swz<D>(v_row_off)) << 4) +
+                   (L16 & 1) * 8;
   }
-  if (wg_item >= n_items) break;
-  const int item = wg_item / p.B;
-  const int b = wg_item - item * p.B;
-  const int id = work[item];
-  const int h = id / p.nbq;
-  const int r = id - h * p.nbq;
-  const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
-  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
-  const u32x4 Vres = head_rsrc(gv + head_off, (uint32_t)N * ROWB);
 
-  const int cbeg = row_ptr[id];
-  const int cend = row_ptr[id + 1];
+  // Query row this lane owns within the block.
+  __device__ __forceinline__ int row_in_block() const { return wave * 32 + l32; }
 
-  // The row's kv-block list is held 64 entries at a time in one VGPR (lane j =
-  // entry j) and read back with v_readlane: no memory operation per tile.
-  const int n_tiles = cend - cbeg;
-  int col_cache = n_tiles > 0 ? col_idx[cbeg + min(lane, n_tiles - 1)] : 0;
-  // first K and V tiles
-  int c_next = 0;
-  if (n_tiles > 0) {
-    c_next = __builtin_amdgcn_readlane(col_cache, 0);
-    LoadK::issue(Kres, c_next * BK, ldsK_wave, tid, k_lane_off);
-    LoadV::issue(Vres, c_next * BK, ldsV_wave, tid, v_lane_off);
-  }
-  // Q^T as MFMA B operand: lane (query l32, half g) holds d = 16 s + 8 g + [0,8)
-  bf16x8 qreg[DS];
-  {
-    int qrow = r * BQ + wave * 32 + l32;
-    qrow = qrow < N ? qrow : N - 1;
-    const uint16_t *qp = gq + head_off + (size_t)qrow * D + 8 * g;
+  __device__ __forceinline__ void issue_k(const u32x4 &Kres, int c) const { LoadK::issue(Kres, c * BK, ldsK_wave, tid, k_lane_off); }
+  __device__ __forceinline__ void issue_v(const u32x4 &Vres, int c) const { LoadV::issue(Vres, c * BK, ldsV_wave, tid, v_lane_off); }
+
+  // Start a row block: `qrow_ptr` points at the D bf16 of this lane's query row.
+  __device__ __forceinline__ void begin(const uint16_t *qrow_ptr) {
+    const uint16_t *qp = qrow_ptr + 8 * g;
 #pragma unroll
     for (int s = 0; s < DS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
     // touch the registers here so that the compiler's wait for these loads sits
-    // in front of the loop and not inside it
+    // in front of the tile loop and not inside it
 #pragma unroll
     for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qreg[s]));
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+    m_run = -INFINITY;
+    l_run = 0.f;
   }
 
-  f32x16 o[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-  float m_run = -INFINITY;  // running max of scaled (log2-domain) logits, shared by lane and lane^32
-  float l_run = 0.f;        // this lane's share of the running row sum
-
-  // K operand row for MFMA row i = l32: swap bits 2 and 3 so that the 8 S^T
-  // values a lane holds per 16-key slab belong to 8 consecutive keys.  With the
-  // XOR swizzle the address of k-slab s is k_addr0 ^ (s << 5).
-  const int krow_in_kb = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
-  const uint32_t k_addr0 = krow_in_kb * ROWB + ((g ^ k_swz<D>(krow_in_kb)) << 4);
-  // transposing V read: 16-lane block -> (d sub-block, key half); lane L16 in block
-  const int L16 = lane & 15;
-  const int blk = lane >> 4;
-  const int v_row_off = 8 * (blk >> 1) + (L16 >> 2);  // + 32 kb + 16 s2 + 4 t
-  uint32_t v_addr[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-    v_addr[db] = v_row_off * ROWB + (((4 * db + 2 * (blk & 1) + ((L16 & 3) >> 1)) ^ v_swz<D>(v_row_off)) << 4) +
-                 (L16 & 1) * 8;
-
-  const float sc = p.scale_log2e;
-
-  for (int ti = 0; ti < n_tiles; ++ti) {
-    const int c = c_next;
-    const bool has_next = ti + 1 < n_tiles;
-    if (has_next) {
-      if (((ti + 1) & 63) == 0) col_cache = col_idx[cbeg + min(ti + 1 + lane, n_tiles - 1)];
-      c_next = __builtin_amdgcn_readlane(col_cache, (ti + 1) & 63);
-    }
-
+  // Fold key/value tile c into the running result.  On entry the K and V loads
+  // of tile c are in flight (K issued first); if has_next, the loads of tile
+  // c_next are issued as soon as the K resp. V buffer is free.  `sc` is
+  // scale * log2(e); keys >= N (last, ragged tile: c == nbk - 1) get zero weight.
+  __device__ __forceinline__ void tile(const u32x4 &Kres, const u32x4 &Vres, int c, bool has_next, int c_next, int N, int nbk,
+                       float sc) {
     // ---- S^T = K Q^T --------------------------------------------------------
-    // K[ci] was issued before V[ci]: V's loads may stay in flight.
+    // K[c] was issued before V[c]: V's loads may stay in flight.
     wait_vmem<LOADS_PER_WAVE>();
     __syncthreads();
     f32x16 s_acc[KB];
@@ -211,11 +155,11 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
       }
     }
     __syncthreads();  // every wave is done with the K tile
-    if (has_next) LoadK::issue(Kres, c_next * BK, ldsK_wave, tid, k_lane_off);
+    if (has_next) issue_k(Kres, c_next);
 
     // ---- online softmax (log2 domain) ----------------------------------------
     float sc_t = sc;  // multiplier still to be applied to s_acc
-    if (c == p.nbk - 1 && (N % BK) != 0) {
+    if (c == nbk - 1 && (N % BK) != 0) {
       // ragged last block: scale now, put keys >= N at -inf, continue with multiplier 1
       const int key0 = c * BK + 8 * g;
 #pragma unroll
@@ -304,14 +248,16 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
       }
     }
     __syncthreads();  // every wave is done with the V tile
-    if (has_next) LoadV::issue(Vres, c_next * BK, ldsV_wave, tid, v_lane_off);
+    if (has_next) issue_v(Vres, c_next);
   }
 
-  // ---- normalise, stage in LDS, store to the block and its repeat targets ----
-  const float l_tot = sum_with_other_half(l_run);
-  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-  __syncthreads();
-  {
+  // Normalise and stage the BQ x D bf16 result in LDS: row i at lds + i * OST.
+  // A row that saw no key is all zero.  Ends with a barrier: the tile is
+  // complete for every thread on return.
+  __device__ __forceinline__ void stage_result() {
+    const float l_tot = sum_with_other_half(l_run);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    __syncthreads();
     char *orow = lds + (wave * 32 + l32) * OST;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -322,8 +268,100 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
         w[1] = pack_bf16(o[db][4 * a + 2] * inv, o[db][4 * a + 3] * inv);
         *reinterpret_cast<u32x2 *>(orow + (32 * db + 8 * a + 4 * g) * 2) = w;
       }
+    __syncthreads();
   }
-  __syncthreads();
+};
+
+template <int D, int BQ, int BK>
+__global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_kernel(
+    const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
+    uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
+    int32_t *counter, const FwdDims p) {
+  using RB = RowBlock<D, BQ, BK>;
+  constexpr int NT = RB::NT, CH = RB::CH, ROWB = RB::ROWB, OST = RB::OST, LDS_BYTES = RB::LDS_BYTES;
+
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // LDS_BYTES + 64 (work-item mailbox)
+  RB rb(lds);
+  const int tid = rb.tid;
+  const int lane = rb.lane;
+  const int N = p.N;
+  const int n_items = p.n_work * p.B;
+  volatile int *const mailbox = reinterpret_cast<volatile int *>(lds + LDS_BYTES);
+  // Persistent workgroups (counter != nullptr): every workgroup pops (work item,
+  // batch index) pairs from per-group counters until all groups are drained, so
+  // uneven rows balance dynamically.  With one group per XCD a workgroup starts
+  // on the group of the XCD it runs on (the heads of a group then share that
+  // XCD's L2) and moves on to the next group, for good, once one is empty.
+  // Otherwise: one workgroup per pair.
+  int cur_group = 0, groups_left = p.n_groups;
+  if (counter && p.n_groups > 1)
+    cur_group = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) % p.n_groups;  // HW_REG_XCC_ID[3:0]
+  ResidencyClock residency;
+  residency.start();
+  for (int wg_item = blockIdx.x;;) {
+  if (counter) {
+    if (tid == 0) {
+      int found = -1;
+      while (groups_left > 0) {
+        const int it = atomicAdd(counter + cur_group, 1);
+        if (it < (p.group_ptr[cur_group + 1] - p.group_ptr[cur_group]) * p.B) {
+          found = p.group_ptr[cur_group] * p.B + it;
+          break;
+        }
+        cur_group = cur_group + 1 == p.n_groups ? 0 : cur_group + 1;
+        --groups_left;
+      }
+      *mailbox = found;
+    }
+    __syncthreads();
+    wg_item = __builtin_amdgcn_readfirstlane(*mailbox);
+    if (wg_item < 0) break;
+  }
+  if (wg_item >= n_items) break;
+  const int item = wg_item / p.B;
+  const int b = wg_item - item * p.B;
+  const int id = work[item];
+  const int h = id / p.nbq;
+  const int r = id - h * p.nbq;
+  const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
+  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
+  const u32x4 Vres = head_rsrc(gv + head_off, (uint32_t)N * ROWB);
+
+  const int cbeg = row_ptr[id];
+  const int cend = row_ptr[id + 1];
+
+  // The row's kv-block list is held 64 entries at a time in one VGPR (lane j =
+  // entry j) and read back with v_readlane: no memory operation per tile.
+  const int n_tiles = cend - cbeg;
+  int col_cache = n_tiles > 0 ? col_idx[cbeg + min(lane, n_tiles - 1)] : 0;
+  // first K and V tiles
+  int c_next = 0;
+  if (n_tiles > 0) {
+    c_next = __builtin_amdgcn_readlane(col_cache, 0);
+    rb.issue_k(Kres, c_next);
+    rb.issue_v(Vres, c_next);
+  }
+  {
+    int qrow = r * BQ + rb.row_in_block();
+    qrow = qrow < N ? qrow : N - 1;
+    rb.begin(gq + head_off + (size_t)qrow * D);
+  }
+  const float sc = p.scale_log2e;
+
+  for (int ti = 0; ti < n_tiles; ++ti) {
+    const int c = c_next;
+    const bool has_next = ti + 1 < n_tiles;
+    if (has_next) {
+      if (((ti + 1) & 63) == 0) col_cache = col_idx[cbeg + min(ti + 1 + lane, n_tiles - 1)];
+      c_next = __builtin_amdgcn_readlane(col_cache, (ti + 1) & 63);
+    }
+
+    rb.tile(Kres, Vres, c, has_next, c_next, N, p.nbk, sc);
+  }
+
+  // ---- normalise, stage in LDS, store to the block and its repeat targets ----
+  rb.stage_result();
   const int fbeg = fan_ptr[item];
   const int fend = fan_ptr[item + 1];
   uint16_t *const out_head = gout + head_off;

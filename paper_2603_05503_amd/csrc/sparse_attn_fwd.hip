@@ -7,6 +7,7 @@
 #include <cstring>
 
 #include "attn_kernel_2wg.h"
+#include "attn_kernel_anchor.h"
 #include "attn_kernel_pipe.h"
 #include "attn_kernel_pp.h"
 #include "calibatt.h"
@@ -45,15 +46,24 @@ int prepare(Kernel kernel, int threads, int smem, DevInfo (&info)[64], int &slot
   return CALIBATT_OK;
 }
 
+// Launches through the call that reports its own status: the runtime's "last error" may still hold
+// an unrelated error left by earlier calls of the host program.
+template <typename Kernel, typename... Args>
+int launch_kernel(Kernel kernel, unsigned grid, int threads, int smem, hipStream_t stream, Args... args) {
+  void *argv[] = {(void *)&args...};
+  return hipLaunchKernel((const void *)kernel, dim3(grid), dim3(threads), argv, smem, stream) == hipSuccess
+             ? CALIBATT_OK
+             : CALIBATT_ERR_LAUNCH;
+}
+
 template <typename Kernel>
 int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, const FwdDims &p, hipStream_t stream) {
   const long long items = (long long)p.n_work * p.B;
   long long grid = items;
   int32_t *counter = a.counter;
   if (counter && items > slots) grid = slots; else counter = nullptr;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), smem, stream, a.q, a.k, a.v, a.out, a.row_ptr,
-                     a.col_idx, a.work, a.fan_ptr, a.fan_dst, counter, p);
-  return hipGetLastError() == hipSuccess ? CALIBATT_OK : CALIBATT_ERR_LAUNCH;
+  return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
+                       a.work, a.fan_ptr, a.fan_dst, counter, p);
 }
 
 // CALIBATT_KERNEL in the environment selects the kernel where its shape is covered: "pp" the
@@ -92,17 +102,60 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
       return enqueue(kernel, PIPE_THREADS, SMEM, slots, a, p, stream);
     }
   }
-  constexpr int TILE_BYTES = BK * D * 2;
-  constexpr int OST = D * 2 + 16;
-  constexpr int LDS_BYTES = (2 * TILE_BYTES > BQ * OST) ? 2 * TILE_BYTES : BQ * OST;
-  constexpr int SMEM = LDS_BYTES + 64;
+  constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64;
   static DevInfo info[64];
   auto kernel = sparse_attn_fwd_kernel<D, BQ, BK>;
   if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
   return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
 }
 
+template <int D>
+int launch_anchor(const FwdPtrs &a, const int32_t *head_ids, const int32_t *q_index, const int32_t *dst_ptr,
+                  const int32_t *dst_idx, const AnchorDims &p, hipStream_t stream) {
+  const long long units = (long long)p.B * p.n_heads * p.nbq;
+  if (units <= 0) return CALIBATT_OK;
+  const long long grid = ANCHOR_XCDS * ((units + ANCHOR_XCDS - 1) / ANCHOR_XCDS);
+  if (grid > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
+  static DevInfo info[64];
+  constexpr int SMEM = AnchorLds<D>::BYTES;
+  auto kernel = anchor_attn_fwd_kernel<D>;
+  int slots = 0;
+  if (int st = prepare(kernel, ANCHOR_BQ * 2, SMEM, info, slots)) return st;
+  return launch_kernel(kernel, (unsigned)grid, ANCHOR_BQ * 2, SMEM, stream, a.q, a.k, a.v, a.out, head_ids, q_index,
+                       dst_ptr, dst_idx, p);
+}
+
 }  // namespace
+
+extern "C" int calibatt_anchor_attn_fwd(const void *q, const void *k, const void *v, void *out, int B, int H,
+                                        int N, int D, const int32_t *head_ids, int n_heads,
+                                        const int32_t *q_index, const int32_t *dst_ptr,
+                                        const int32_t *dst_idx, int n_q, float scale, void *stream) {
+  if (!q || !k || !v || !out) return CALIBATT_ERR_NULL;
+  if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || n_heads < 0 || n_q < 0) return CALIBATT_ERR_SHAPE;
+  if (!(D == 64 || D == 128)) return CALIBATT_ERR_UNSUPPORTED;
+  if (out == q || out == k || out == v) return CALIBATT_ERR_SHAPE;
+  if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
+  if (n_heads == 0 || n_q == 0) return CALIBATT_OK;
+  if (!head_ids || !q_index || !dst_ptr || !dst_idx) return CALIBATT_ERR_NULL;
+  FwdPtrs a{};
+  a.q = (const uint16_t *)q;
+  a.k = (const uint16_t *)k;
+  a.v = (const uint16_t *)v;
+  a.out = (uint16_t *)out;
+  AnchorDims p;
+  p.B = B;
+  p.H = H;
+  p.N = N;
+  p.n_heads = n_heads;
+  p.n_q = n_q;
+  p.nbq = (n_q + ANCHOR_BQ - 1) / ANCHOR_BQ;
+  p.nbk = (N + ANCHOR_BK - 1) / ANCHOR_BK;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  hipStream_t s = (hipStream_t)stream;
+  if (D == 128) return launch_anchor<128>(a, head_ids, q_index, dst_ptr, dst_idx, p, s);
+  return launch_anchor<64>(a, head_ids, q_index, dst_ptr, dst_idx, p, s);
+}
 
 extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void *v, void *out, int B,
                                         int H, int N, int D, int block_q, int block_k,

@@ -41,7 +41,7 @@ def test_header_symbols_exported():
     header = open(os.path.join(ROOT, "include", "calibatt.h")).read()
     names = set(re.findall(r"^(?:int|const char \*)\s*(calibatt_\w+)\s*\(", header, flags=re.M))
     assert {"calibatt_pattern_sizes", "calibatt_compile_pattern", "calibatt_sparse_attn_fwd",
-            "calibatt_strerror", "calibatt_version"} <= names
+            "calibatt_anchor_map", "calibatt_anchor_attn_fwd", "calibatt_strerror", "calibatt_version"} <= names
     lib = ctypes.CDLL(pkg.library_path())
     for n in names:
         assert hasattr(lib, n), n
