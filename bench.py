@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one elementwise kernel that reads and writes 1 GiB each (reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
+    ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
+    ap.add_argument("--anchor-k", type=int, nargs="*", default=None,
+                    help="anchor rows per frame to time (default: the k of the paper's table)")
     return ap.parse_args()
 
 
@@ -63,6 +66,41 @@ def time_launches(pkg, torch, q, k, v, out, dp, scale, steps, warmup):
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     ev = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
     return wall_ms, sum(ev) / len(ev), ev[len(ev) // 2]
+
+
+# Supplement, table "Spatial repetition attention benchmark": milliseconds of FA3 on one H100 at the
+# Wan 480p shape for k anchor rows per frame (k = 30 is full attention).  Another machine: context only.
+PAPER_ANCHOR_MS_H100 = {30: 31.62, 15: 18.60, 10: 11.52, 5: 5.99, 4: 4.79, 3: 3.72, 2: 2.77, 1: 1.54}
+
+
+def anchor_table(pkg, torch, q, k, v, out, wl, steps, ks=None):
+    """Anchor-row attention (Section 3.3) on all heads at the video geometry of the workload, for the
+    k of the paper's table: kernel milliseconds by HIP events, speed-up over k = rows per frame."""
+    F, Hs, Ws = wl.geometry
+    head_ids = torch.arange(wl.H, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+    rows = []
+    for kk in sorted(ks if ks else PAPER_ANCHOR_MS_H100, reverse=True):
+        if not 1 <= kk <= Hs:
+            continue
+        amap = pkg.anchor_map(wl.N, F, Hs, Ws, kk).to_device()
+        pkg.anchor_attn_fwd(q, k, v, out, head_ids, amap, wl.scale)
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            pkg.anchor_attn_fwd(q, k, v, out, head_ids, amap, wl.scale)
+            b.record(stream)
+            torch.cuda.synchronize()
+            ms.append(a.elapsed_time(b))
+        t = sum(ms) / len(ms)
+        flops = 4.0 * amap.n_q * wl.N * wl.D * wl.H * wl.B
+        rows.append({"k": kk, "computed_queries": amap.n_q, "ms": t, "tflops": flops / (t * 1e-3) / 1e12,
+                     "paper_h100_fa3_ms": PAPER_ANCHOR_MS_H100.get(kk)})
+    for r in rows:
+        r["speedup_vs_all_rows"] = rows[0]["ms"] / r["ms"]
+    return rows
 
 
 def cpu_oracle_baseline(wl, n_blocks):
@@ -218,6 +256,8 @@ def main():
             "traffic": profiled_traffic(args),
         },
     }
+    if not args.no_anchor and getattr(wl, "geometry", None) is not None:
+        result["anchor_rows"] = anchor_table(pkg, torch, q, k, v, out, wl, max(3, args.steps // 4), args.anchor_k)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_oracle_baseline(wl, args.cpu_blocks)
     print(json.dumps(result))

@@ -325,6 +325,7 @@ class Workload:
     k: Optional[np.ndarray] = None
     v: Optional[np.ndarray] = None
     stats: Dict = field(default_factory=dict)
+    geometry: Optional[tuple] = None  # (frames, rows per frame, columns) of the video tokens
 
     @property
     def nbq(self) -> int:
@@ -376,7 +377,8 @@ def make_workload(
         d = cfg["density"] if density is None else density
         p = cfg["repeat"] if repeat_frac is None else repeat_frac
         mask, repeat, stats = calibrated_like_mask(seed, H, N, blk, geom, d, p, repeat_mode=repeat_mode)
-    wl = Workload(name, cfg["B"], H, N, D, blk, blk, 1.0 / math.sqrt(D), mask, repeat, stats=stats)
+    wl = Workload(name, cfg["B"], H, N, D, blk, blk, 1.0 / math.sqrt(D), mask, repeat, stats=stats,
+                  geometry=(geom.frames, geom.rows, geom.cols))
     if with_qkv:
         wl.q, wl.k, wl.v = make_qkv(seed + 500, cfg["B"], H, N, D, geom, alpha=cfg["alpha"], qk_gain=qk_gain)
     return wl
