@@ -1,5 +1,5 @@
-"""CPU oracle for block-sparse attention with repeated query blocks and for the
-spatial-row anchor scheme.
+"""CPU oracle for block-sparse attention with repeated query blocks, for the
+spatial-row anchor scheme and for the calibration steps that produce a mask.
 
 TEST INFRASTRUCTURE ONLY.  Plain, slow, fp64 NumPy written from the paper's
 definitions; it shares no code with the HIP library and must never be imported
@@ -7,7 +7,7 @@ by the product package.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
 ``cpu_baseline`` leg of ``bench.py`` use it.
 
 Pin status (see tests/test_oracle_pins.py, tests/test_pattern_oracle.py and
-tests/test_anchor_oracle_pins.py): every function below is pinned by
+tests/test_anchor_oracle_pins.py, tests/test_calibration_oracle_pins.py): every function below is pinned by
 brute force on tiny inputs, a library routine on a special case, closed forms
 and invariants.  No function is "parity unpinned".
 """
@@ -19,4 +19,5 @@ from .attention import (  # noqa: F401
     sparse_attention_blocks,
 )
 from .anchor import anchor_attention, anchor_rows, anchor_token_maps, nearest_anchor  # noqa: F401
+from .calibration import block_energy, epsilon_schedule, schedule_base_level, select_blocks, select_row, vote  # noqa: F401
 from .pattern import compile_pattern, pattern_sizes, PatternError  # noqa: F401
