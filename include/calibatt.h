@@ -223,6 +223,57 @@ int calibatt_anchor_attn_fwd(const void *q, const void *k, const void *v, void *
                              const int32_t *q_index, const int32_t *dst_ptr, const int32_t *dst_idx,
                              int n_q, float scale, void *stream);
 
+/*
+ * Calibration steps that turn attention maps into a block mask (Section 3.2).
+ * They run offline, once per (timestep, layer, head) and calibration prompt;
+ * the energy kernel is the one part that touches N x N work.
+ *
+ * calibatt_block_energy (Eq. 5): energy[b][h][r][c] = the softmax mass
+ * (Section 2, Eq. 1, logits scale * q k^T over all N keys) that the queries of
+ * block r put on the keys of block c, averaged over the queries of the block
+ * (a short last block averages over the rows it has, so every block-row sums
+ * to 1).  The N x N map is never stored.
+ *   q, k    DEVICE, bf16, contiguous [B][H][N][D]; read only.
+ *   energy  DEVICE, fp32, contiguous [B][H][ceil(N/block_q)][ceil(N/block_k)];
+ *           every entry is written.  Same bits on every run.
+ *   stream  hipStream_t (NULL = default stream).  The call only enqueues work.
+ * Supported: D in {64, 128}, block_q and block_k in {64, 128}, and
+ * ceil(N/block_k) small enough for the per-workgroup partial sums to fit in
+ * LDS next to two K tiles (N up to 262144 at least).
+ * Errors: NULL, SHAPE, UNSUPPORTED, LAUNCH.
+ */
+int calibatt_block_energy(const void *q, const void *k, float *energy, int B, int H, int N, int D,
+                          int block_q, int block_k, float scale, void *stream);
+
+/*
+ * calibatt_select_blocks (Eq. 6): for each of n_rows block-rows of nbk
+ * energies, keep the smallest set of blocks whose energies sum to at least
+ * eps: sort descending (equal energies: lower column first), take the shortest
+ * prefix whose running sum, accumulated in double in that order, reaches eps;
+ * a row whose total stays below eps keeps every block.
+ *   energy  HOST, fp32 [n_rows][nbk]       mask  HOST, uint8 [n_rows][nbk], 1 = kept
+ * Errors: NULL, SHAPE (n_rows < 0, nbk <= 0, eps not a number), NOMEM.
+ */
+int calibatt_select_blocks(const float *energy, int64_t n_rows, int nbk, double eps, uint8_t *mask);
+
+/*
+ * calibatt_vote_masks (Eq. 8-9): masks of n_prompts calibration prompts, each
+ * n entries (any non-zero byte = kept) -> out[i] = 1 where count_i / n_prompts
+ * >= rho (compared in double), else 0.  HOST buffers; out may alias masks[0..n).
+ * Errors: NULL, SHAPE (n_prompts <= 0, n < 0, rho not a number).
+ */
+int calibatt_vote_masks(const uint8_t *masks, int n_prompts, int64_t n, double rho, uint8_t *out);
+
+/*
+ * Energy threshold of diffusion step t of T (Eq. 7): A + (C - A) exp(-k t / T),
+ * t = 0 the highest-noise step.  Returns NaN when T <= 0.
+ * calibatt_schedule_base_level: the base level A the paper uses in the
+ * many-step regime for sequence length N, 0.796 + 1.41e-6 N (with C = 0.99,
+ * k = 16; supplement, "Hyperparameter search for energy threshold schedule").
+ */
+double calibatt_epsilon_schedule(int t, int T, double A, double C, double k);
+double calibatt_schedule_base_level(int N);
+
 /* Static, NUL-terminated description of a status code. */
 const char *calibatt_strerror(int status);
 

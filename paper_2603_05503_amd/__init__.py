@@ -12,11 +12,16 @@ from .binding import (  # noqa: F401
     HostPattern,
     anchor_attn_fwd,
     anchor_map,
+    block_energy,
     compile_pattern,
+    epsilon_schedule,
     library_path,
     load_library,
     pattern_sizes,
+    schedule_base_level,
+    select_blocks,
     sparse_attn_fwd,
     strerror,
     version,
+    vote_masks,
 )

@@ -78,6 +78,17 @@ def load_library():
         C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
         C.c_float, C.c_void_p,
     ]
+    lib.calibatt_block_energy.restype = C.c_int
+    lib.calibatt_block_energy.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                          C.c_int, C.c_int, C.c_float, C.c_void_p]
+    lib.calibatt_select_blocks.restype = C.c_int
+    lib.calibatt_select_blocks.argtypes = [C.POINTER(C.c_float), C.c_int64, C.c_int, C.c_double, u8p]
+    lib.calibatt_vote_masks.restype = C.c_int
+    lib.calibatt_vote_masks.argtypes = [u8p, C.c_int, C.c_int64, C.c_double, u8p]
+    lib.calibatt_epsilon_schedule.restype = C.c_double
+    lib.calibatt_epsilon_schedule.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double]
+    lib.calibatt_schedule_base_level.restype = C.c_double
+    lib.calibatt_schedule_base_level.argtypes = [C.c_int]
     lib.calibatt_strerror.restype = C.c_char_p
     lib.calibatt_strerror.argtypes = [C.c_int]
     lib.calibatt_version.restype = C.c_int
@@ -306,3 +317,64 @@ def anchor_attn_fwd(q, k, v, out, head_ids, amap: DeviceAnchorMap, scale: float,
     if st != 0:
         raise CalibattError(st, "calibatt_anchor_attn_fwd")
     return out
+
+
+def block_energy(q, k, block_q: int, block_k: int, scale: float, out=None, stream=None):
+    """calibatt_block_energy on torch bf16 CUDA tensors [B, H, N, D]; returns the fp32 CUDA tensor
+    [B, H, ceil(N/block_q), ceil(N/block_k)] (``out`` if given)."""
+    import torch
+
+    lib = load_library()
+    for t in (q, k):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
+            raise ValueError("q, k must be contiguous bf16 CUDA tensors [B, H, N, D]")
+    if q.shape != k.shape:
+        raise ValueError("q and k must have the same shape")
+    B, H, N, D = q.shape
+    shape = (B, H, -(-N // block_q), -(-N // block_k))
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=q.device)
+    elif not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == shape):
+        raise ValueError(f"out must be a contiguous fp32 CUDA tensor of shape {shape}")
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = lib.calibatt_block_energy(q.data_ptr(), k.data_ptr(), out.data_ptr(), B, H, N, D, block_q, block_k,
+                                   float(scale), C.c_void_p(stream))
+    if st != 0:
+        raise CalibattError(st, "calibatt_block_energy")
+    return out
+
+
+def select_blocks(energy, eps: float) -> np.ndarray:
+    """calibatt_select_blocks on a host array [..., nbk] (converted to fp32): uint8 mask of the same shape."""
+    lib = load_library()
+    e = np.ascontiguousarray(energy, dtype=np.float32)
+    if e.ndim < 1 or e.shape[-1] == 0:
+        raise CalibattError(-2, "calibatt_select_blocks")
+    mask = np.empty(e.shape, np.uint8)
+    st = lib.calibatt_select_blocks(_ptr(e, C.c_float), e.size // e.shape[-1], e.shape[-1], float(eps),
+                                    _ptr(mask, C.c_uint8))
+    if st != 0:
+        raise CalibattError(st, "calibatt_select_blocks")
+    return mask
+
+
+def vote_masks(masks, rho: float) -> np.ndarray:
+    """calibatt_vote_masks on a host array [n_prompts, ...]: uint8 mask of the trailing shape."""
+    lib = load_library()
+    m = np.ascontiguousarray(masks, dtype=np.uint8)
+    if m.ndim < 1 or m.shape[0] == 0:
+        raise CalibattError(-2, "calibatt_vote_masks")
+    out = np.empty(m.shape[1:], np.uint8)
+    st = lib.calibatt_vote_masks(_ptr(m, C.c_uint8), m.shape[0], out.size, float(rho), _ptr(out, C.c_uint8))
+    if st != 0:
+        raise CalibattError(st, "calibatt_vote_masks")
+    return out
+
+
+def epsilon_schedule(t: int, T: int, A: float, Cc: float, k: float) -> float:
+    return float(load_library().calibatt_epsilon_schedule(int(t), int(T), float(A), float(Cc), float(k)))
+
+
+def schedule_base_level(N: int) -> float:
+    return float(load_library().calibatt_schedule_base_level(int(N)))

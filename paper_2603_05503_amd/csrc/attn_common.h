@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "calibatt.h"
 
 namespace calibatt_dev {
@@ -152,5 +154,22 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
   return a + b;
 }
 
+// Sum of x over the 64 lanes of the wave, delivered to every lane, as a fixed
+// butterfly (the same order of additions in every run): xor 1, 2 (quad
+// permutes), 4 (half-row mirror), 8 (row mirror) inside rows of 16 lanes, then
+// the 16-lane and 32-lane swaps across rows.
+__device__ __forceinline__ float wave_sum(float x) {
+  auto dpp = [](float v, auto ctrl) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value,
+                                                                 0xf, 0xf, false));
+  };
+  x += dpp(x, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
+  x += dpp(x, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
+  x += dpp(x, std::integral_constant<int, 0x141>{});  // row_half_mirror
+  x += dpp(x, std::integral_constant<int, 0x140>{});  // row_mirror
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return sum_with_other_half(a + b);
+}
 
 }  // namespace calibatt_dev

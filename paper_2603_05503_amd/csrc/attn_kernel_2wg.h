@@ -94,6 +94,10 @@ struct RowBlock {
   __device__ __forceinline__ int row_in_block() const { return wave * 32 + l32; }
 
   __device__ __forceinline__ void issue_k(const u32x4 &Kres, int c) const { LoadK::issue(Kres, c * BK, ldsK_wave, tid, k_lane_off); }
+  // K tile c into the LDS window at byte offset `buf_off` (a multiple of TILE_BYTES)
+  __device__ __forceinline__ void issue_k_at(const u32x4 &Kres, int c, uint32_t buf_off) const {
+    LoadK::issue(Kres, c * BK, ldsK_wave + buf_off, tid, k_lane_off);
+  }
   __device__ __forceinline__ void issue_v(const u32x4 &Vres, int c) const { LoadV::issue(Vres, c * BK, ldsV_wave, tid, v_lane_off); }
 
   // Start a row block: `qrow_ptr` points at the D bf16 of this lane's query row.
@@ -113,6 +117,40 @@ struct RowBlock {
     l_run = 0.f;
   }
 
+  // S^T = K Q^T for the K tile at byte offset `buf_off` of the LDS window:
+  // s_acc[kb][v] = dot(key 32 kb + 16 (v >> 3) + 8 g + (v & 7), query l32), unscaled.
+  __device__ __forceinline__ void scores(uint32_t buf_off, f32x16 (&s_acc)[KB]) const {
+    const char *const kbuf = ldsK + buf_off;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.f;
+    // k-slab outer, key sub-block inner: consecutive MFMAs hit different
+    // accumulators; the A operands of slab s+1 are read while slab s multiplies.
+    bf16x8 ka[2][KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+      ka[0][kb] = *reinterpret_cast<const bf16x8 *>(kbuf + (k_addr0 + kb * 32 * ROWB));
+#pragma unroll
+    for (int s = 0; s < DS; ++s) {
+      if (s + 1 < DS) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+          ka[(s + 1) & 1][kb] =
+              *reinterpret_cast<const bf16x8 *>(kbuf + ((k_addr0 ^ ((s + 1) << 5)) + kb * 32 * ROWB));
+      }
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][kb], qreg[s], s_acc[kb], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab 0
+#pragma unroll
+    for (int s = 0; s < DS; ++s) {
+      if (s + 1 < DS) __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab s+1
+      __builtin_amdgcn_sched_group_barrier(0x008, KB, 0);                  // MFMAs of slab s
+    }
+  }
+
   // Fold key/value tile c into the running result.  On entry the K and V loads
   // of tile c are in flight (K issued first); if has_next, the loads of tile
   // c_next are issued as soon as the K resp. V buffer is free.  `sc` is
@@ -124,36 +162,7 @@ struct RowBlock {
     wait_vmem<LOADS_PER_WAVE>();
     __syncthreads();
     f32x16 s_acc[KB];
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.f;
-    // k-slab outer, key sub-block inner: consecutive MFMAs hit different
-    // accumulators; the A operands of slab s+1 are read while slab s multiplies.
-    {
-      bf16x8 ka[2][KB];
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-        ka[0][kb] = *reinterpret_cast<const bf16x8 *>(ldsK + (k_addr0 + kb * 32 * ROWB));
-#pragma unroll
-      for (int s = 0; s < DS; ++s) {
-        if (s + 1 < DS) {
-#pragma unroll
-          for (int kb = 0; kb < KB; ++kb)
-            ka[(s + 1) & 1][kb] =
-                *reinterpret_cast<const bf16x8 *>(ldsK + ((k_addr0 ^ ((s + 1) << 5)) + kb * 32 * ROWB));
-        }
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-          s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][kb], qreg[s], s_acc[kb], 0, 0, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab 0
-#pragma unroll
-      for (int s = 0; s < DS; ++s) {
-        if (s + 1 < DS) __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab s+1
-        __builtin_amdgcn_sched_group_barrier(0x008, KB, 0);                  // MFMAs of slab s
-      }
-    }
+    scores(0, s_acc);
     __syncthreads();  // every wave is done with the K tile
     if (has_next) issue_k(Kres, c_next);
 

@@ -1,0 +1,127 @@
+// Block energy of an attention map without materialising it (paper, Section
+// 3.2, Eq. 5): E[r][c] = mean over the queries of block r of the softmax mass
+// they put on the keys of block c.  gfx950 (MI355X), bf16 in, fp32 out.
+//
+// One workgroup per (batch, head, query block), two passes over all key tiles
+// with the QK^T engine of the attention kernels (RowBlock::scores; a lane owns
+// one query and half of the tile's keys):
+//   pass 1  running row max and row sum (online softmax statistics);
+//   pass 2  p = exp2(s - max) / sum per entry, summed over the lane's keys,
+//           then over the wave's 32 queries with a fixed butterfly, one fp32
+//           partial per (wave, key block) in LDS; at the end the partials of
+//           the workgroup's waves are added in wave order and divided by the
+//           number of rows the block has.
+// No V, so both LDS tile buffers hold K: tile c+1 streams in while tile c is
+// multiplied, one barrier per tile.  Work units are placed like those of the
+// anchor kernel (contiguous ranges per XCD) since all query blocks of a head
+// walk the same K tiles in step.  Every addition order is fixed: the result is
+// the same bits on every run.
+#pragma once
+#include "attn_kernel_2wg.h"
+
+namespace calibatt_dev {
+
+struct EnergyDims {
+  int B, H, N, nbq, nbk;
+  float scale_log2e;
+};
+
+constexpr int ENERGY_XCDS = 8;
+
+template <int D, int BQ, int BK>
+struct EnergyLds {
+  using RB = RowBlock<D, BQ, BK>;
+  static constexpr int PART_OFF = 2 * RB::TILE_BYTES;  // float[NW][nbk] partial sums behind the two K buffers
+  static __host__ __device__ constexpr long long bytes(int nbk) { return PART_OFF + (long long)RB::NW * nbk * 4; }
+};
+
+template <int D, int BQ, int BK>
+__global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void block_energy_kernel(
+    const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, float *__restrict__ gE, const EnergyDims p) {
+  using RB = RowBlock<D, BQ, BK>;
+  constexpr int NT = RB::NT, NW = RB::NW, KB = RB::KB, ROWB = RB::ROWB, TILE_BYTES = RB::TILE_BYTES;
+
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // EnergyLds::bytes(nbk)
+
+  const int xcd = blockIdx.x % ENERGY_XCDS;
+  const int slot = blockIdx.x / ENERGY_XCDS;
+  const long long units = (long long)p.B * p.H * p.nbq;
+  const long long lo = units * xcd / ENERGY_XCDS;
+  const long long hi = units * (xcd + 1) / ENERGY_XCDS;
+  if (slot >= hi - lo) return;
+  const int unit = (int)(lo + slot);
+  const int r = unit % p.nbq;
+  const int bh = unit / p.nbq;  // b * H + h
+
+  RB rb(lds);
+  const int tid = rb.tid;
+  const int N = p.N;
+  const size_t head_off = (size_t)bh * (size_t)N * D;
+  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
+  float *const part = reinterpret_cast<float *>(lds + EnergyLds<D, BQ, BK>::PART_OFF);
+  const int rows_valid = min(BQ, N - r * BQ);
+
+  rb.issue_k_at(Kres, 0, 0);
+  const bool row_valid = rb.row_in_block() < rows_valid;
+  rb.begin(gq + head_off + (size_t)(r * BQ + (row_valid ? rb.row_in_block() : 0)) * D);
+  const float sc = p.scale_log2e;
+  const bool ragged = (N % BK) != 0;
+
+  float m_run = -INFINITY, l_run = 0.f, weight = 0.f;
+  // Tiles of both passes form one sequence t = pass * nbk + c; tile t sits in buffer t & 1.
+  const int n_steps = 2 * p.nbk;
+  for (int t = 0; t < n_steps; ++t) {
+    const bool second = t >= p.nbk;
+    const int c = second ? t - p.nbk : t;
+    wait_vmem<0>();
+    __syncthreads();  // tile t has landed for every wave; everyone is done with the other buffer
+    if (t + 1 < n_steps) rb.issue_k_at(Kres, c + 1 < p.nbk ? c + 1 : 0, ((t + 1) & 1) * TILE_BYTES);
+    f32x16 s[KB];
+    rb.scores((t & 1) * TILE_BYTES, s);
+    // scaled logits (log2 domain); keys >= N of the ragged last tile at -inf
+    const bool tail = ragged && c == p.nbk - 1;
+    const int key0 = c * BK + 8 * rb.g;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
+        s[kb][v] = (tail && key >= N) ? -INFINITY : s[kb][v] * sc;
+      }
+    if (!second) {
+      float m_loc = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m_loc = fmaxf(m_loc, s[kb][v]);
+      const float m_new = fmaxf(m_run, max_with_other_half(m_loc));
+      float psum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(s[kb][v] - m_new);
+      l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum;
+      m_run = m_new;
+      if (c == p.nbk - 1) weight = row_valid ? 1.0f / sum_with_other_half(l_run) : 0.f;
+    } else {
+      float e = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) e += __builtin_amdgcn_exp2f(s[kb][v] - m_run);
+      e = wave_sum(e * weight);
+      if (rb.lane == 0) part[rb.wave * p.nbk + c] = e;
+    }
+  }
+  __syncthreads();
+  const float inv_rows = 1.0f / (float)rows_valid;
+  float *const out = gE + ((size_t)bh * p.nbq + r) * (size_t)p.nbk;
+  for (int c = tid; c < p.nbk; c += NT) {
+    float e = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) e += part[w * p.nbk + c];
+    out[c] = e * inv_rows;
+  }
+}
+
+}  // namespace calibatt_dev

@@ -1,0 +1,56 @@
+// Host-side calibration steps (paper, Section 3.2): block selection by energy
+// (Eq. 6), threshold schedule (Eq. 7), cross-prompt vote (Eq. 8-9).
+#include <stdint.h>
+
+#include <algorithm>
+#include <cmath>
+#include <limits>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "calibatt.h"
+
+extern "C" int calibatt_select_blocks(const float *energy, int64_t n_rows, int nbk, double eps, uint8_t *mask) {
+  if (!energy || !mask) return CALIBATT_ERR_NULL;
+  if (n_rows < 0 || nbk <= 0 || std::isnan(eps)) return CALIBATT_ERR_SHAPE;
+  std::vector<int32_t> order;
+  try {
+    order.resize((size_t)nbk);
+  } catch (const std::bad_alloc &) {
+    return CALIBATT_ERR_NOMEM;
+  }
+  for (int64_t row = 0; row < n_rows; ++row) {
+    const float *e = energy + row * nbk;
+    uint8_t *m = mask + row * nbk;
+    std::iota(order.begin(), order.end(), 0);
+    // descending energy; among equals the lower column first (stable sort of ascending columns)
+    std::stable_sort(order.begin(), order.end(), [e](int32_t a, int32_t b) { return e[a] > e[b]; });
+    std::fill(m, m + nbk, (uint8_t)0);
+    double total = 0.0;
+    for (int i = 0; i < nbk; ++i) {
+      m[order[i]] = 1;
+      total += (double)e[order[i]];
+      if (total >= eps) break;
+    }
+  }
+  return CALIBATT_OK;
+}
+
+extern "C" int calibatt_vote_masks(const uint8_t *masks, int n_prompts, int64_t n, double rho, uint8_t *out) {
+  if (!masks || !out) return CALIBATT_ERR_NULL;
+  if (n_prompts <= 0 || n < 0 || std::isnan(rho)) return CALIBATT_ERR_SHAPE;
+  for (int64_t i = 0; i < n; ++i) {
+    int count = 0;
+    for (int p = 0; p < n_prompts; ++p) count += masks[(int64_t)p * n + i] != 0;
+    out[i] = ((double)count / (double)n_prompts >= rho) ? 1 : 0;
+  }
+  return CALIBATT_OK;
+}
+
+extern "C" double calibatt_epsilon_schedule(int t, int T, double A, double C, double k) {
+  if (T <= 0) return std::numeric_limits<double>::quiet_NaN();
+  return A + (C - A) * std::exp(-k * (double)t / (double)T);
+}
+
+extern "C" double calibatt_schedule_base_level(int N) { return 0.796 + 1.41e-6 * (double)N; }

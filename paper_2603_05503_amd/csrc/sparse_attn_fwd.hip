@@ -8,6 +8,7 @@
 
 #include "attn_kernel_2wg.h"
 #include "attn_kernel_anchor.h"
+#include "attn_kernel_energy.h"
 #include "attn_kernel_pipe.h"
 #include "attn_kernel_pp.h"
 #include "calibatt.h"
@@ -125,7 +126,61 @@ int launch_anchor(const FwdPtrs &a, const int32_t *head_ids, const int32_t *q_in
                        dst_ptr, dst_idx, p);
 }
 
+// Dynamic LDS of the energy kernel grows with the number of key blocks; one generous ceiling is
+// registered per kernel and device, launches above it are refused.
+constexpr int ENERGY_MAX_LDS = 128 * 1024;
+
+template <int D, int BQ, int BK>
+int launch_energy(const uint16_t *q, const uint16_t *k, float *energy, const EnergyDims &p, hipStream_t stream) {
+  const long long units = (long long)p.B * p.H * p.nbq;
+  const long long grid = ENERGY_XCDS * ((units + ENERGY_XCDS - 1) / ENERGY_XCDS);
+  if (grid > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
+  const long long smem = EnergyLds<D, BQ, BK>::bytes(p.nbk);
+  if (smem > ENERGY_MAX_LDS) return CALIBATT_ERR_UNSUPPORTED;
+  auto kernel = block_energy_kernel<D, BQ, BK>;
+  static bool ready[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CALIBATT_ERR_LAUNCH;
+  if (!ready[dev]) {
+    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ENERGY_MAX_LDS) !=
+        hipSuccess)
+      return CALIBATT_ERR_LAUNCH;
+    ready[dev] = true;
+  }
+  return launch_kernel(kernel, (unsigned)grid, BQ * 2, (int)smem, stream, q, k, energy, p);
+}
+
 }  // namespace
+
+extern "C" int calibatt_block_energy(const void *q, const void *k, float *energy, int B, int H, int N, int D,
+                                     int block_q, int block_k, float scale, void *stream) {
+  if (!q || !k || !energy) return CALIBATT_ERR_NULL;
+  if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || block_q <= 0 || block_k <= 0) return CALIBATT_ERR_SHAPE;
+  if (!(D == 64 || D == 128) || !(block_q == 64 || block_q == 128) || !(block_k == 64 || block_k == 128))
+    return CALIBATT_ERR_UNSUPPORTED;
+  if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
+  EnergyDims p;
+  p.B = B;
+  p.H = H;
+  p.N = N;
+  p.nbq = (N + block_q - 1) / block_q;
+  p.nbk = (N + block_k - 1) / block_k;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  const uint16_t *qq = (const uint16_t *)q, *kk = (const uint16_t *)k;
+  hipStream_t s = (hipStream_t)stream;
+#define CALIBATT_CASE(d, bq, bk) \
+  if (D == d && block_q == bq && block_k == bk) return launch_energy<d, bq, bk>(qq, kk, energy, p, s);
+  CALIBATT_CASE(128, 128, 128)
+  CALIBATT_CASE(128, 128, 64)
+  CALIBATT_CASE(128, 64, 128)
+  CALIBATT_CASE(128, 64, 64)
+  CALIBATT_CASE(64, 128, 128)
+  CALIBATT_CASE(64, 128, 64)
+  CALIBATT_CASE(64, 64, 128)
+  CALIBATT_CASE(64, 64, 64)
+#undef CALIBATT_CASE
+  return CALIBATT_ERR_UNSUPPORTED;
+}
 
 extern "C" int calibatt_anchor_attn_fwd(const void *q, const void *k, const void *v, void *out, int B, int H,
                                         int N, int D, const int32_t *head_ids, int n_heads,

@@ -1,0 +1,118 @@
+"""GPU parity of the block-energy kernel (Eq. 5) against the fp64 oracle, through
+the C ABI, and the calibration chain built on it (Eq. 6, 8-9 -> pattern ->
+sparse forward).
+
+Tolerance of the energies: logits come from bf16 products accumulated in fp32
+(relative error ~1e-6 of a logit of magnitude <= ~50, i.e. <= 1e-4 absolute in
+the exponent), exp2 is the hardware approximation (~1 ulp), sums are fp32 over
+<= 128 x N terms in a fixed tree: relative error of an energy <= ~5e-4.  The
+test allows 2e-3 relative plus 2e-7 absolute (entries near the fp32 floor)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import block_energy, select_blocks, sparse_attention
+from tests.parity_utils import bits_to_f64, from_dev, to_dev
+from workloads import f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 2e-3, 2e-7
+
+
+def _qk(seed, B, H, N, D, gain=1.0):
+    rng = np.random.default_rng(seed)
+    q = f32_to_bf16_bits((gain * rng.standard_normal((B, H, N, D))).astype(np.float32))
+    k = f32_to_bf16_bits((gain * rng.standard_normal((B, H, N, D))).astype(np.float32))
+    return q, k
+
+
+CASES = [
+    # B, H, N, D, bq, bk, gain, scale
+    (1, 2, 300, 64, 64, 64, 1.0, None),      # ragged, odd number of key tiles
+    (2, 2, 777, 128, 128, 128, 2.0, None),   # ragged, batch 2
+    (1, 1, 1000, 128, 64, 128, 2.0, None),
+    (1, 1, 1000, 128, 128, 64, 2.0, None),
+    (1, 3, 384, 64, 128, 128, 1.0, None),    # exact multiple, three key tiles
+    (1, 1, 50, 128, 128, 128, 1.0, None),    # shorter than one block
+    (1, 2, 512, 128, 128, 128, 2.0, -0.1),   # negative scale
+    (1, 1, 640, 128, 128, 128, 5.0, 0.25),   # sharp softmax: logits of magnitude ~ 100
+    (1, 9, 256, 64, 64, 64, 1.0, None),      # more heads than XCD ranges
+]
+
+
+@pytest.mark.parametrize("B,H,N,D,bq,bk,gain,scale", CASES)
+def test_block_energy_parity(lib, B, H, N, D, bq, bk, gain, scale):
+    import torch
+
+    print(f"energy parity B={B} H={H} N={N} D={D} bq={bq} bk={bk} gain={gain} scale={scale}", flush=True)
+    q, k = _qk(31 + N + D + bq + bk, B, H, N, D, gain)
+    scale = 1 / math.sqrt(D) if scale is None else scale
+    tq, tk = to_dev(q), to_dev(k)
+    E = lib.block_energy(tq, tk, bq, bk, scale)
+    torch.cuda.synchronize()
+    got = E.cpu().numpy().astype(np.float64)
+    want = block_energy(q, k, scale, bq, bk)
+    assert got.shape == want.shape
+    assert np.isfinite(got).all()
+    np.testing.assert_allclose(got, want, rtol=RTOL, atol=ATOL)
+    np.testing.assert_allclose(got.sum(axis=-1), 1.0, rtol=0, atol=2e-4)
+    # same bits on a second run into a poisoned buffer
+    E2 = torch.full_like(E, float("nan"))
+    lib.block_energy(tq, tk, bq, bk, scale, out=E2)
+    torch.cuda.synchronize()
+    assert torch.equal(E, E2)
+
+
+def test_uniform_attention_gives_block_sizes(lib):
+    import torch
+
+    print("energy uniform", flush=True)
+    N, D, bq, bk = 700, 128, 128, 64
+    q = np.zeros((1, 1, N, D), np.uint16)
+    _, k = _qk(5, 1, 1, N, D)
+    E = lib.block_energy(to_dev(q), to_dev(k), bq, bk, 1.0).cpu().numpy()
+    sizes = np.array([min((c + 1) * bk, N) - c * bk for c in range(-(-N // bk))]) / N
+    np.testing.assert_allclose(E[0, 0], np.broadcast_to(sizes, E[0, 0].shape), rtol=1e-5)
+
+
+def test_calibration_chain(lib):
+    """Energies -> per-prompt selection -> vote -> compiled pattern -> sparse
+    forward.  Masks from the GPU energies are checked for validity against the
+    oracle's energies (the two may differ where a running sum sits within the
+    energy tolerance of the threshold); the sparse output stays close to dense
+    attention because the kept blocks carry >= eps of every row's mass."""
+    import torch
+
+    print("calibration chain", flush=True)
+    B, H, N, D, blk, eps, tol = 1, 2, 1500, 128, 128, 0.9, 2e-3
+    nb = -(-N // blk)
+    masks = []
+    for prompt in range(3):
+        q, k = _qk(200 + prompt, B, H, N, D, 2.5)
+        E = lib.block_energy(to_dev(q), to_dev(k), blk, blk, 1 / math.sqrt(D)).cpu().numpy()
+        m = lib.select_blocks(E, eps)
+        Eo = block_energy(q, k, 1 / math.sqrt(D), blk, blk)
+        kept = (Eo * m).sum(axis=-1)
+        assert (kept >= eps - tol).all()
+        lo, hi = select_blocks(Eo, eps - tol).sum(axis=-1), select_blocks(Eo, eps + tol).sum(axis=-1)
+        assert (m.sum(axis=-1) >= lo).all() and (m.sum(axis=-1) <= hi).all()
+        masks.append(m[0])
+    mask = lib.vote_masks(np.stack(masks), 0.5)
+    assert mask.shape == (H, nb, nb) and 0 < mask.mean() < 1
+    # run the last prompt through the sparse kernel with its own mask: >= eps of the mass kept
+    rng = np.random.default_rng(9)
+    v = f32_to_bf16_bits(rng.standard_normal((B, H, N, D)).astype(np.float32))
+    own = masks[-1]
+    dp = lib.compile_pattern(own, None, H, N, blk, blk, 1).to_device()
+    out = torch.empty_like(to_dev(q))
+    lib.sparse_attn_fwd(to_dev(q), to_dev(k), to_dev(v), out, dp, 1 / math.sqrt(D))
+    torch.cuda.synchronize()
+    got = bits_to_f64(from_dev(out))
+    want_sparse = sparse_attention(q, k, v, own, None, 1 / math.sqrt(D), blk, blk)
+    assert np.abs(got - want_sparse).max() <= 2e-2
+    dense = sparse_attention(q, k, v, np.ones_like(own), None, 1 / math.sqrt(D), blk, blk)
+    rel = np.linalg.norm(got - dense) / np.linalg.norm(dense)
+    print(f"density {own.mean():.3f}, rel. L2 distance to dense attention {rel:.3f}", flush=True)
+    assert rel < 0.5
