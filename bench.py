@@ -44,6 +44,7 @@ def parse_args():
                     help="also run one elementwise kernel that reads and writes 1 GiB each (reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
+    ap.add_argument("--no-energy", action="store_true", help="skip the block-energy (calibration) kernel")
     ap.add_argument("--anchor-k", type=int, nargs="*", default=None,
                     help="anchor rows per frame to time (default: the k of the paper's table)")
     return ap.parse_args()
@@ -101,6 +102,27 @@ def anchor_table(pkg, torch, q, k, v, out, wl, steps, ks=None):
     for r in rows:
         r["speedup_vs_all_rows"] = rows[0]["ms"] / r["ms"]
     return rows
+
+
+def energy_leg(pkg, torch, q, k, wl, steps):
+    """Block-energy kernel (Section 3.2, Eq. 5) on all heads of the workload: kernel milliseconds by
+    HIP events; flops = two QK^T passes = 4 N^2 D per head."""
+    stream = torch.cuda.current_stream()
+    E = pkg.block_energy(q, k, wl.block_q, wl.block_k, wl.scale)
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        pkg.block_energy(q, k, wl.block_q, wl.block_k, wl.scale, out=E)
+        b.record(stream)
+        torch.cuda.synchronize()
+        ms.append(a.elapsed_time(b))
+    t = sum(ms) / len(ms)
+    flops = 4.0 * wl.N * wl.N * wl.D * wl.H * wl.B
+    row_sums = E.sum(dim=-1)
+    return {"ms": t, "tflops": flops / (t * 1e-3) / 1e12,
+            "max_row_sum_error": float((row_sums - 1).abs().max())}
 
 
 def cpu_oracle_baseline(wl, n_blocks):
@@ -258,6 +280,8 @@ def main():
     }
     if not args.no_anchor and getattr(wl, "geometry", None) is not None:
         result["anchor_rows"] = anchor_table(pkg, torch, q, k, v, out, wl, max(3, args.steps // 4), args.anchor_k)
+    if not args.no_energy:
+        result["block_energy"] = energy_leg(pkg, torch, q, k, wl, max(3, args.steps // 4))
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_oracle_baseline(wl, args.cpu_blocks)
     print(json.dumps(result))

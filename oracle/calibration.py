@@ -23,6 +23,20 @@ import numpy as np
 from .attention import bf16_bits_to_f64
 
 
+def _energy_of_rows(q_rows: np.ndarray, kf: np.ndarray, scale: float, block_k: int) -> np.ndarray:
+    """Eq. 5 for one query block given as its fp64 rows: vector over key blocks."""
+    n = kf.shape[0]
+    nbk = -(-n // block_k)
+    s = scale * (q_rows @ kf.T)
+    s = s - s.max(axis=1, keepdims=True)
+    p = np.exp(s)
+    p = p / p.sum(axis=1, keepdims=True)  # Eq. 1
+    out = np.empty(nbk, dtype=np.float64)
+    for c in range(nbk):
+        out[c] = p[:, c * block_k : (c + 1) * block_k].sum() / p.shape[0]
+    return out
+
+
 def block_energy(q_bits: np.ndarray, k_bits: np.ndarray, scale: float, block_q: int, block_k: int) -> np.ndarray:
     """E[b, h, r, c] = mean over the queries of block r of the softmax mass they
     put on the keys of block c (Eq. 5).  fp64 [B, H, ceil(N/block_q), ceil(N/block_k)]."""
@@ -34,14 +48,18 @@ def block_energy(q_bits: np.ndarray, k_bits: np.ndarray, scale: float, block_q: 
             qf = bf16_bits_to_f64(q_bits[b, h])
             kf = bf16_bits_to_f64(k_bits[b, h])
             for r in range(nbq):
-                rows = slice(r * block_q, min((r + 1) * block_q, N))
-                s = scale * (qf[rows] @ kf.T)
-                s = s - s.max(axis=1, keepdims=True)
-                p = np.exp(s)
-                p = p / p.sum(axis=1, keepdims=True)  # Eq. 1
-                n_rows = p.shape[0]
-                for c in range(nbk):
-                    out[b, h, r, c] = p[:, c * block_k : (c + 1) * block_k].sum() / n_rows
+                out[b, h, r] = _energy_of_rows(qf[r * block_q : min((r + 1) * block_q, N)], kf, scale, block_k)
+    return out
+
+
+def block_energy_rows(q_bits, k_bits, scale: float, block_q: int, block_k: int, items):
+    """Eq. 5 for selected block-rows only: for each (b, h, r) in ``items`` the
+    fp64 vector over key blocks.  Same arithmetic as ``block_energy``."""
+    N = q_bits.shape[2]
+    out = []
+    for (b, h, r) in items:
+        qf = bf16_bits_to_f64(q_bits[b, h, r * block_q : min((r + 1) * block_q, N)])
+        out.append(_energy_of_rows(qf, bf16_bits_to_f64(k_bits[b, h]), scale, block_k))
     return out
 
 

@@ -56,6 +56,15 @@ def test_block_rows_sum_to_one_and_match_the_attention_oracles_probabilities():
             np.testing.assert_allclose(E[:, :, r, c], blk.sum(axis=(2, 3)) / blk.shape[2], rtol=1e-12, atol=1e-15)
 
 
+def test_selected_rows_equal_the_full_computation():
+    rng = np.random.default_rng(6)
+    q, k = _bits(rng, (2, 2, 37, 8), 2.0), _bits(rng, (2, 2, 37, 8), 2.0)
+    E = cal.block_energy(q, k, 0.3, 8, 5)
+    items = [(0, 0, 0), (1, 1, 4), (0, 1, 2)]
+    for (b, h, r), e in zip(items, cal.block_energy_rows(q, k, 0.3, 8, 5, items)):
+        assert (e == E[b, h, r]).all()
+
+
 def test_uniform_attention_gives_block_sizes():
     rng = np.random.default_rng(4)
     N, D, bq, bk = 23, 4, 5, 6

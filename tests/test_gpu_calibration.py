@@ -12,7 +12,7 @@ import math
 import numpy as np
 import pytest
 
-from oracle import block_energy, select_blocks, sparse_attention
+from oracle import block_energy, block_energy_rows, select_blocks, sparse_attention
 from tests.parity_utils import bits_to_f64, from_dev, to_dev
 from workloads import f32_to_bf16_bits
 
@@ -75,6 +75,25 @@ def test_uniform_attention_gives_block_sizes(lib):
     E = lib.block_energy(to_dev(q), to_dev(k), bq, bk, 1.0).cpu().numpy()
     sizes = np.array([min((c + 1) * bk, N) - c * bk for c in range(-(-N // bk))]) / N
     np.testing.assert_allclose(E[0, 0], np.broadcast_to(sizes, E[0, 0].shape), rtol=1e-5)
+
+
+def test_wan480_sampled_parity(lib):
+    """Full Wan-480p sequence length on a few heads with positionally structured
+    q, k (the bench workload's recipe): sampled block-rows against the oracle,
+    every block-row sums to 1."""
+    import torch
+    from workloads import make_workload
+
+    print("energy wan480", flush=True)
+    wl = make_workload("wan480", heads=3, qk_gain=1.5)
+    E = lib.block_energy(to_dev(wl.q), to_dev(wl.k), wl.block_q, wl.block_k, wl.scale)
+    torch.cuda.synchronize()
+    got = E.cpu().numpy().astype(np.float64)
+    assert got.shape == (1, 3, wl.nbq, wl.nbk) and np.isfinite(got).all()
+    np.testing.assert_allclose(got.sum(axis=-1), 1.0, rtol=0, atol=2e-4)
+    items = [(0, 0, 0), (0, 1, 100), (0, 2, wl.nbq - 1), (0, 1, 17), (0, 2, 200)]
+    for (b, h, r), want in zip(items, block_energy_rows(wl.q, wl.k, wl.scale, wl.block_q, wl.block_k, items)):
+        np.testing.assert_allclose(got[b, h, r], want, rtol=RTOL, atol=ATOL)
 
 
 def test_calibration_chain(lib):
