@@ -78,28 +78,42 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void block_energy_kern
     if (t + 1 < n_steps) rb.issue_k_at(Kres, c + 1 < p.nbk ? c + 1 : 0, ((t + 1) & 1) * TILE_BYTES);
     f32x16 s[KB];
     rb.scores((t & 1) * TILE_BYTES, s);
-    // scaled logits (log2 domain); keys >= N of the ragged last tile at -inf
-    const bool tail = ragged && c == p.nbk - 1;
-    const int key0 = c * BK + 8 * rb.g;
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
-        s[kb][v] = (tail && key >= N) ? -INFINITY : s[kb][v] * sc;
-      }
-    if (!second) {
-      float m_loc = -INFINITY;
+    // Work on the raw products with the scale folded into the exponent's FMA; only the ragged last
+    // tile is scaled up front so that its keys >= N can sit at -inf (multiplier 1 from then on).
+    float sc_t = sc;
+    if (ragged && c == p.nbk - 1) {
+      const int key0 = c * BK + 8 * rb.g;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) m_loc = fmaxf(m_loc, s[kb][v]);
-      const float m_new = fmaxf(m_run, max_with_other_half(m_loc));
+        for (int v = 0; v < 16; ++v) {
+          const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
+          s[kb][v] = key < N ? s[kb][v] * sc : -INFINITY;
+        }
+      sc_t = 1.0f;
+    }
+    if (!second) {
+      // largest scaled logit of the tile: the largest product, or the smallest under a negative scale
+      float m_loc;
+      if (sc_t >= 0.f) {
+        m_loc = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) m_loc = fmaxf(m_loc, s[kb][v]);
+      } else {
+        m_loc = INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) m_loc = fminf(m_loc, s[kb][v]);
+      }
+      const float m_new = fmaxf(m_run, max_with_other_half(m_loc * sc_t));
       float psum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(s[kb][v] - m_new);
+        for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], sc_t, -m_new));
       l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum;
       m_run = m_new;
       if (c == p.nbk - 1) weight = row_valid ? 1.0f / sum_with_other_half(l_run) : 0.f;
@@ -108,7 +122,7 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void block_energy_kern
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) e += __builtin_amdgcn_exp2f(s[kb][v] - m_run);
+        for (int v = 0; v < 16; ++v) e += __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], sc_t, -m_run));
       e = wave_sum(e * weight);
       if (rb.lane == 0) part[rb.wave * p.nbk + c] = e;
     }
