@@ -83,6 +83,10 @@ typedef struct calibatt_pattern {
   int32_t *work_counter;     /* NULL, or DEVICE int32[16] workspace, see calibatt_sparse_attn_fwd */
   int32_t n_groups;          /* 1, or CALIBATT_GROUPS for CALIBATT_ORDER_XCD_HEADS */
   int32_t group_ptr[CALIBATT_GROUPS + 1]; /* segment g of `work` is [group_ptr[g], group_ptr[g+1]) */
+  /* Optional interval form of the kept-block lists (calibatt_encode_intervals): when both are
+   * non-NULL the forward reads them and never touches col_idx, which may then be NULL. */
+  const int32_t *iv_ptr;     /* [H*nbq + 1] offsets into iv */
+  const uint32_t *iv;        /* interval words, see calibatt_encode_intervals */
 } calibatt_pattern;
 
 /*
@@ -132,7 +136,10 @@ int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repeat, int H, 
  * pattern  HOST struct holding DEVICE pointers (see above).  The same pattern
  *          serves every batch index (supplement Section A: one mask for the
  *          conditional and unconditional branch).  Index contents cannot be
- *          validated on the device: build them with calibatt_compile_pattern.
+ *          validated on the device: build them with calibatt_compile_pattern
+ *          (and calibatt_encode_intervals for the optional interval form,
+ *          which replaces col_idx: pattern bytes shrink from 4 per kept block
+ *          to 4 per run of consecutive kept blocks).
  *          pattern->work_counter selects how work items reach the GPU:
  *          NULL  - one workgroup per (computed query block, batch index), in
  *                  schedule order;
@@ -273,6 +280,54 @@ int calibatt_vote_masks(const uint8_t *masks, int n_prompts, int64_t n, double r
  */
 double calibatt_epsilon_schedule(int t, int T, double A, double C, double k);
 double calibatt_schedule_base_level(int N);
+
+/*
+ * Skip-list tools of the supplement (Section A.2 "Skip-List Memory
+ * Optimization", Section A.3 "Timestep Mask Sharing").  All HOST buffers.
+ *
+ * calibatt_encode_intervals: the flat ("1D") interval layout of the kept-block
+ * lists of a compiled pattern - every row as its maximal runs of consecutive
+ * key blocks.  One 32-bit word per interval: low 16 bits = first key block of
+ * the run, high 16 bits = number of kept blocks of the row before the run; each
+ * row ends with one more word carrying (0, kept blocks of the row), so a row of
+ * n runs takes n + 1 words and a run's length is the difference of two
+ * neighbouring high halves.  Needs nbk <= 65535.
+ *   row_ptr [n_rows + 1], col_idx: as written by calibatt_compile_pattern
+ *   iv_ptr  [n_rows + 1]  offsets into iv          iv [iv_cap]  words
+ *   n_words               number of words needed (always written when non-NULL)
+ * iv_ptr or iv may be NULL to learn n_words only.
+ * Errors: NULL, SHAPE (n_rows < 0, a column >= 65536, a row longer than 65535,
+ * columns of a row not strictly ascending), BUFFER_TOO_SMALL (iv_cap < n_words).
+ */
+int calibatt_encode_intervals(const int32_t *row_ptr, const int32_t *col_idx, int64_t n_rows,
+                              int32_t *iv_ptr, uint32_t *iv, int64_t iv_cap, int64_t *n_words);
+
+/*
+ * calibatt_merge_intervals: interval merging by percentile.  width = the
+ * nearest-rank pct-th percentile of the interval counts of the n_rows rows
+ * (the smallest count w such that at least pct percent of the rows have <= w
+ * intervals; at least 1).  Rows with more intervals get their smallest gaps
+ * between neighbouring intervals filled with kept blocks (the leftmost among
+ * equal gaps first) until they have `width` intervals; other rows are copied.
+ *   mask [n_rows][nbk] uint8, non-zero = kept     out [n_rows][nbk], 0 / 1;
+ *   may alias mask.                                width: may be NULL.
+ * Errors: NULL, SHAPE (n_rows < 0, nbk <= 0, pct outside (0, 100]), NOMEM.
+ */
+int calibatt_merge_intervals(const uint8_t *mask, int64_t n_rows, int nbk, double pct, uint8_t *out,
+                             int32_t *width);
+
+/*
+ * calibatt_share_timesteps: masks[T][n] of one (layer, head), one per diffusion
+ * step.  Steps are visited in ascending order; a step joins the first cluster
+ * (in order of creation) in which the IoU of its skipped-block set with that of
+ * every member is >= tau (two masks that skip nothing: IoU 1), else it founds
+ * a new cluster.  cluster[t] receives the cluster of step t, shared[c][n] the
+ * OR of the kept blocks of the members of cluster c (first *n_clusters rows
+ * written; the buffer holds T rows), 0 / 1.
+ * Errors: NULL, SHAPE (T <= 0, n < 0, tau not a number), NOMEM.
+ */
+int calibatt_share_timesteps(const uint8_t *masks, int T, int64_t n, double tau, int32_t *cluster,
+                             uint8_t *shared, int32_t *n_clusters);
 
 /* Static, NUL-terminated description of a status code. */
 const char *calibatt_strerror(int status);

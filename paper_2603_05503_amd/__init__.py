@@ -14,12 +14,15 @@ from .binding import (  # noqa: F401
     anchor_map,
     block_energy,
     compile_pattern,
+    encode_intervals,
     epsilon_schedule,
     library_path,
     load_library,
+    merge_intervals,
     pattern_sizes,
     schedule_base_level,
     select_blocks,
+    share_timesteps,
     sparse_attn_fwd,
     strerror,
     version,

@@ -31,6 +31,7 @@ class _CPattern(C.Structure):
         ("work_counter", C.c_void_p),
         ("n_groups", C.c_int32),
         ("group_ptr", C.c_int32 * 9),
+        ("iv_ptr", C.c_void_p), ("iv", C.c_void_p),
     ]
 
 
@@ -89,6 +90,13 @@ def load_library():
     lib.calibatt_epsilon_schedule.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double]
     lib.calibatt_schedule_base_level.restype = C.c_double
     lib.calibatt_schedule_base_level.argtypes = [C.c_int]
+    u32p = C.POINTER(C.c_uint32)
+    lib.calibatt_encode_intervals.restype = C.c_int
+    lib.calibatt_encode_intervals.argtypes = [i32p, i32p, C.c_int64, i32p, u32p, C.c_int64, i64p]
+    lib.calibatt_merge_intervals.restype = C.c_int
+    lib.calibatt_merge_intervals.argtypes = [u8p, C.c_int64, C.c_int, C.c_double, u8p, i32p]
+    lib.calibatt_share_timesteps.restype = C.c_int
+    lib.calibatt_share_timesteps.argtypes = [u8p, C.c_int, C.c_int64, C.c_double, i32p, u8p, i32p]
     lib.calibatt_strerror.restype = C.c_char_p
     lib.calibatt_strerror.argtypes = [C.c_int]
     lib.calibatt_version.restype = C.c_int
@@ -161,8 +169,13 @@ class HostPattern:
     n_groups: int = 1
     group_ptr: Optional[np.ndarray] = None
 
-    def to_device(self, device="cuda", persistent=True) -> "DevicePattern":
-        return DevicePattern(self, device, persistent)
+    def to_device(self, device="cuda", persistent=True, intervals=False) -> "DevicePattern":
+        """``intervals=True`` uploads the interval form of the kept-block lists instead of col_idx."""
+        return DevicePattern(self, device, persistent, intervals)
+
+    def encode_intervals(self):
+        """(iv_ptr int32 [rows + 1], iv uint32 words) via calibatt_encode_intervals."""
+        return encode_intervals(self.row_ptr, self.col_idx)
 
 
 def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1) -> HostPattern:
@@ -201,12 +214,15 @@ class DevicePattern:
 
     _NAMES = ("row_ptr", "col_idx", "repeat_src", "work", "fan_ptr", "fan_dst")
 
-    def __init__(self, hp: HostPattern, device="cuda", persistent=True):
+    def __init__(self, hp: HostPattern, device="cuda", persistent=True, intervals=False):
         import torch
 
         self.host = hp
         self.tensors = {}
+        self.intervals = bool(intervals)
         for name in self._NAMES:
+            if intervals and name == "col_idx":
+                continue
             a = getattr(hp, name)
             t = torch.from_numpy(np.ascontiguousarray(a if a.size else np.zeros(1, np.int32)))
             self.tensors[name] = t.to(device)
@@ -214,7 +230,16 @@ class DevicePattern:
         for f in ("H", "N", "block_q", "block_k", "nbq", "nbk", "n_work", "n_repeat", "order", "max_row", "nnz"):
             setattr(c, f, getattr(hp, f))
         for name in self._NAMES:
-            setattr(c, name, self.tensors[name].data_ptr())
+            setattr(c, name, self.tensors[name].data_ptr() if name in self.tensors else None)
+        if intervals:
+            iv_ptr, iv = hp.encode_intervals()
+            self.tensors["iv_ptr"] = torch.from_numpy(iv_ptr).to(device)
+            self.tensors["iv"] = torch.from_numpy(iv.view(np.int32)).to(device)
+            c.iv_ptr = self.tensors["iv_ptr"].data_ptr()
+            c.iv = self.tensors["iv"].data_ptr()
+        else:
+            c.iv_ptr = None
+            c.iv = None
         # int32[16] workspace of the persistent-workgroup scheduler (kept zero between calls)
         self.counter = torch.zeros(16, dtype=torch.int32, device=device) if persistent else None
         c.work_counter = self.counter.data_ptr() if persistent else None
@@ -227,6 +252,12 @@ class DevicePattern:
     @property
     def nnz(self) -> int:
         return self.host.nnz
+
+    @property
+    def index_bytes(self) -> int:
+        """Bytes of the kept-block lists on the GPU (col_idx, or iv_ptr + iv in the interval form)."""
+        names = ("iv_ptr", "iv") if self.intervals else ("col_idx",)
+        return sum(self.tensors[n].numel() * 4 for n in names)
 
 
 def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
@@ -378,3 +409,58 @@ def epsilon_schedule(t: int, T: int, A: float, Cc: float, k: float) -> float:
 
 def schedule_base_level(N: int) -> float:
     return float(load_library().calibatt_schedule_base_level(int(N)))
+
+
+def encode_intervals(row_ptr, col_idx):
+    """calibatt_encode_intervals: (iv_ptr int32 [rows + 1], iv uint32 words)."""
+    lib = load_library()
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    if ci.size == 0:
+        ci = np.zeros(1, np.int32)
+    n_rows = rp.size - 1
+    n_words = C.c_int64(0)
+    st = lib.calibatt_encode_intervals(_ptr(rp, C.c_int32), _ptr(ci, C.c_int32), n_rows, None, None, 0, C.byref(n_words))
+    if st != 0:
+        raise CalibattError(st, "calibatt_encode_intervals")
+    iv_ptr = np.empty(n_rows + 1, np.int32)
+    iv = np.empty(max(n_words.value, 1), np.uint32)
+    st = lib.calibatt_encode_intervals(_ptr(rp, C.c_int32), _ptr(ci, C.c_int32), n_rows, _ptr(iv_ptr, C.c_int32),
+                                       _ptr(iv, C.c_uint32), iv.size, C.byref(n_words))
+    if st != 0:
+        raise CalibattError(st, "calibatt_encode_intervals")
+    return iv_ptr, iv[: n_words.value]
+
+
+def merge_intervals(mask, pct: float):
+    """calibatt_merge_intervals over all rows of ``mask[..., nbk]``: (merged uint8 mask, width)."""
+    lib = load_library()
+    m = np.ascontiguousarray(mask, dtype=np.uint8)
+    if m.ndim < 1 or m.shape[-1] == 0:
+        raise CalibattError(-2, "calibatt_merge_intervals")
+    out = np.empty_like(m)
+    width = C.c_int32(0)
+    st = lib.calibatt_merge_intervals(_ptr(m, C.c_uint8), m.size // m.shape[-1], m.shape[-1], float(pct),
+                                      _ptr(out, C.c_uint8), C.byref(width))
+    if st != 0:
+        raise CalibattError(st, "calibatt_merge_intervals")
+    return out, int(width.value)
+
+
+def share_timesteps(masks, tau: float):
+    """calibatt_share_timesteps on ``masks[T, ...]`` of one (layer, head): (cluster ids int32 [T],
+    shared masks uint8 [n_clusters, ...])."""
+    lib = load_library()
+    m = np.ascontiguousarray(masks, dtype=np.uint8)
+    if m.ndim < 1 or m.shape[0] == 0:
+        raise CalibattError(-2, "calibatt_share_timesteps")
+    T = m.shape[0]
+    n = m.size // T
+    cluster = np.empty(T, np.int32)
+    shared = np.empty_like(m)
+    n_clusters = C.c_int32(0)
+    st = lib.calibatt_share_timesteps(_ptr(m, C.c_uint8), T, n, float(tau), _ptr(cluster, C.c_int32),
+                                      _ptr(shared, C.c_uint8), C.byref(n_clusters))
+    if st != 0:
+        raise CalibattError(st, "calibatt_share_timesteps")
+    return cluster, shared[: n_clusters.value].copy()

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libcalibatt.so")
 
-SOURCES = ["compile_pattern.cpp", "anchor_map.cpp", "calibration.cpp", "sparse_attn_fwd.hip"]
+SOURCES = ["compile_pattern.cpp", "anchor_map.cpp", "calibration.cpp", "skiplist.cpp", "sparse_attn_fwd.hip"]
 
 # Packed fp32 VALU forms are switched off for all device code.
 HIP_FLAGS = [

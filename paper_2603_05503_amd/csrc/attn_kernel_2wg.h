@@ -281,16 +281,27 @@ struct RowBlock {
   }
 };
 
-template <int D, int BQ, int BK>
+// Kept-block columns of a row held in LDS when the pattern comes as intervals
+// (IV = true): this many at a time, behind the work-item mailbox.
+constexpr int IV_COLS = 2048;
+
+// IV = false: the kept key blocks of a row are read from col_idx (row_ptr gives
+// the slice).  IV = true: col_idx is not touched; `iv_ptr` / `iv` hold every
+// row as runs of consecutive key blocks, one word per run (low half = first
+// block, high half = kept blocks of the row before the run) plus a terminating
+// word per row, and the workgroup expands them into LDS.
+template <int D, int BQ, int BK, bool IV = false>
 __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_kernel(
     const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
     uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
-    int32_t *counter, const FwdDims p) {
+    int32_t *counter, const FwdDims p, const int32_t *__restrict__ iv_ptr, const uint32_t *__restrict__ iv) {
   using RB = RowBlock<D, BQ, BK>;
   constexpr int NT = RB::NT, CH = RB::CH, ROWB = RB::ROWB, OST = RB::OST, LDS_BYTES = RB::LDS_BYTES;
 
-  extern __shared__ __attribute__((aligned(1024))) char lds[];  // LDS_BYTES + 64 (work-item mailbox)
+  // LDS_BYTES + 64 (work-item mailbox) [+ IV_COLS * 4 (column list) if IV]
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  int *const cols = reinterpret_cast<int *>(lds + LDS_BYTES + 64);
   RB rb(lds);
   const int tid = rb.tid;
   const int lane = rb.lane;
@@ -343,7 +354,22 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   // The row's kv-block list is held 64 entries at a time in one VGPR (lane j =
   // entry j) and read back with v_readlane: no memory operation per tile.
   const int n_tiles = cend - cbeg;
-  int col_cache = n_tiles > 0 ? col_idx[cbeg + min(lane, n_tiles - 1)] : 0;
+  // IV: entries [chunk_lo, chunk_lo + IV_COLS) of the list are expanded from the
+  // row's runs into LDS; every thread takes runs tid, tid + NT, ...
+  int chunk_lo = 0;
+  auto expand_runs = [&]() {
+    const int ib = iv_ptr[id], ie = iv_ptr[id + 1] - 1;  // the last word only terminates the row
+    for (int i = ib + tid; i < ie; i += NT) {
+      const uint32_t w = iv[i], w_next = iv[i + 1];
+      const int start = (int)(w & 0xffffu), before = (int)(w >> 16), len = (int)(w_next >> 16) - before;
+      const int j0 = max(0, chunk_lo - before), j1 = min(len, chunk_lo + IV_COLS - before);
+      for (int j = j0; j < j1; ++j) cols[before + j - chunk_lo] = start + j;
+    }
+    __syncthreads();
+  };
+  auto col_at = [&](int entry) { return IV ? cols[entry - chunk_lo] : col_idx[cbeg + entry]; };
+  if constexpr (IV) expand_runs();  // the previous item's readers are behind the barrier that ended it
+  int col_cache = n_tiles > 0 ? col_at(min(lane, n_tiles - 1)) : 0;
   // first K and V tiles
   int c_next = 0;
   if (n_tiles > 0) {
@@ -362,7 +388,16 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     const int c = c_next;
     const bool has_next = ti + 1 < n_tiles;
     if (has_next) {
-      if (((ti + 1) & 63) == 0) col_cache = col_idx[cbeg + min(ti + 1 + lane, n_tiles - 1)];
+      if (((ti + 1) & 63) == 0) {
+        if constexpr (IV) {
+          if ((ti + 1) % IV_COLS == 0) {
+            __syncthreads();  // every wave has taken its entries of the chunk that is replaced
+            chunk_lo = ti + 1;
+            expand_runs();
+          }
+        }
+        col_cache = col_at(min(ti + 1 + lane, n_tiles - 1));
+      }
       c_next = __builtin_amdgcn_readlane(col_cache, (ti + 1) & 63);
     }
 

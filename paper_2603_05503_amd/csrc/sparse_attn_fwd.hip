@@ -21,6 +21,8 @@ struct FwdPtrs {
   uint16_t *out;
   const int32_t *row_ptr, *col_idx, *work, *fan_ptr, *fan_dst;
   int32_t *counter;
+  const int32_t *iv_ptr;  // interval form of the kept-block lists, or NULL
+  const uint32_t *iv;
 };
 
 // Per-device launch facts, looked up once per kernel and device.
@@ -57,14 +59,19 @@ int launch_kernel(Kernel kernel, unsigned grid, int threads, int smem, hipStream
              : CALIBATT_ERR_LAUNCH;
 }
 
-template <typename Kernel>
+// TAKES_IV: the kernel has the two trailing interval-list parameters (the two-workgroup kernel).
+template <bool TAKES_IV, typename Kernel>
 int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, const FwdDims &p, hipStream_t stream) {
   const long long items = (long long)p.n_work * p.B;
   long long grid = items;
   int32_t *counter = a.counter;
   if (counter && items > slots) grid = slots; else counter = nullptr;
-  return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
-                       a.work, a.fan_ptr, a.fan_dst, counter, p);
+  if constexpr (TAKES_IV)
+    return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
+                         a.work, a.fan_ptr, a.fan_dst, counter, p, a.iv_ptr, a.iv);
+  else
+    return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
+                         a.work, a.fan_ptr, a.fan_dst, counter, p);
 }
 
 // CALIBATT_KERNEL in the environment selects the kernel where its shape is covered: "pp" the
@@ -84,6 +91,13 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
   if (items <= 0) return CALIBATT_OK;
   if (items > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
   int slots = 0;
+  if (a.iv) {  // interval-encoded pattern: read by the two-workgroup kernel only
+    static DevInfo info[64];
+    constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + IV_COLS * 4;
+    auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, true>;
+    if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
+    return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
+  }
   const Variant variant = wanted_variant();
   if constexpr (BQ <= BK) {
     if (variant == Variant::PingPong) {
@@ -91,7 +105,7 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
       constexpr int SMEM = PpLds<D, BQ, BK>::BYTES;
       auto kernel = sparse_attn_fwd_pp_kernel<D, BQ, BK>;
       if (int st = prepare(kernel, BQ * 4, SMEM, info, slots)) return st;
-      return enqueue(kernel, BQ * 4, SMEM, slots, a, p, stream);
+      return enqueue<false>(kernel, BQ * 4, SMEM, slots, a, p, stream);
     }
   }
   if constexpr (D == 128 && BQ == 128 && BK == 128) {
@@ -100,14 +114,14 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
       constexpr int SMEM = PipeLds<D, BQ, BK>::BYTES;
       auto kernel = sparse_attn_fwd_pipe_kernel<D, BQ, BK>;
       if (int st = prepare(kernel, PIPE_THREADS, SMEM, info, slots)) return st;
-      return enqueue(kernel, PIPE_THREADS, SMEM, slots, a, p, stream);
+      return enqueue<false>(kernel, PIPE_THREADS, SMEM, slots, a, p, stream);
     }
   }
   constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64;
   static DevInfo info[64];
-  auto kernel = sparse_attn_fwd_kernel<D, BQ, BK>;
+  auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, false>;
   if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
-  return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
+  return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
 }
 
 template <int D>
@@ -230,9 +244,12 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
     return CALIBATT_ERR_PATTERN_MISMATCH;
   for (int g = 0; g < pattern->n_groups; ++g)
     if (pattern->group_ptr[g] > pattern->group_ptr[g + 1]) return CALIBATT_ERR_PATTERN_MISMATCH;
+  const bool intervals = pattern->iv_ptr && pattern->iv;
+  if ((pattern->iv_ptr != nullptr) != (pattern->iv != nullptr)) return CALIBATT_ERR_NULL;
   if (!pattern->row_ptr || !pattern->work || !pattern->fan_ptr ||
-      (pattern->nnz > 0 && !pattern->col_idx) || (pattern->n_repeat > 0 && !pattern->fan_dst))
+      (pattern->nnz > 0 && !pattern->col_idx && !intervals) || (pattern->n_repeat > 0 && !pattern->fan_dst))
     return CALIBATT_ERR_NULL;
+  if (intervals && nbk > 65535) return CALIBATT_ERR_UNSUPPORTED;
   if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
 
   FwdPtrs a;
@@ -246,6 +263,8 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
   a.fan_ptr = pattern->fan_ptr;
   a.fan_dst = pattern->fan_dst;
   a.counter = pattern->work_counter;
+  a.iv_ptr = intervals ? pattern->iv_ptr : nullptr;
+  a.iv = intervals ? pattern->iv : nullptr;
   FwdDims p;
   p.B = B;
   p.H = H;
