@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one elementwise kernel that reads and writes 1 GiB each (reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
+    ap.add_argument("--intervals", action="store_true",
+                    help="hand the pattern over as runs of consecutive key blocks instead of block indices")
     ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
     ap.add_argument("--no-energy", action="store_true", help="skip the block-energy (calibration) kernel")
     ap.add_argument("--anchor-k", type=int, nargs="*", default=None,
@@ -205,7 +207,7 @@ def main():
     t0 = time.perf_counter()
     hp = pkg.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, args.order)
     compile_ms = (time.perf_counter() - t0) * 1e3
-    dp = hp.to_device(persistent=not args.no_persistent)
+    dp = hp.to_device(persistent=not args.no_persistent, intervals=args.intervals)
     q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
     out = torch.empty_like(q)
     tile_flops = 4.0 * wl.block_q * wl.block_k * wl.D
@@ -262,6 +264,8 @@ def main():
             "schedule_order": args.order,
             "persistent_workgroups": not args.no_persistent,
             "pattern_compile_ms": compile_ms,
+            "pattern_form": "intervals" if args.intervals else "indices",
+            "pattern_index_bytes": dp.index_bytes,
         },
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "kernel_ms_mean": ev_mean_ms,
