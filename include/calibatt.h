@@ -171,6 +171,30 @@ int calibatt_sparse_attn_fwd(const void *q, const void *k, const void *v, void *
                              const calibatt_pattern *pattern, float scale, void *stream);
 
 /*
+ * The same forward on tensors that are not packed [B][H][N][D]: element
+ * (b, h, n, d) of q, k and v sits at b*in->b + h*in->h + n*in->n + d from the
+ * respective pointer, element (b, h, n, d) of out at the same expression with
+ * `out_strides`.  The D axis stays contiguous.  This covers the layouts
+ * attention layers produce without a transpose: [B][N][H][D] (b = N*H*D, h = D,
+ * n = H*D) and q, k, v as slices of one fused projection output
+ * [B][N][3][H][D] (b = 3*N*H*D, h = D, n = 3*H*D, three base pointers).
+ * Requirements: every stride a multiple of 8 elements, n >= D, pointers
+ * 16-byte aligned, (N-1)*n*2 + D*2 < 2^32 bytes; the caller guarantees that
+ * distinct (b, h, n) rows of out do not overlap.  Everything else as in
+ * calibatt_sparse_attn_fwd, which is this call with packed strides.
+ * Errors: as calibatt_sparse_attn_fwd; SHAPE also for strides or alignment
+ * that break the requirements.
+ */
+typedef struct calibatt_strides {
+  int64_t b, h, n; /* in elements */
+} calibatt_strides;
+int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, const void *v, void *out, int B,
+                                     int H, int N, int D, int block_q, int block_k,
+                                     const calibatt_pattern *pattern, float scale,
+                                     const calibatt_strides *in_strides,
+                                     const calibatt_strides *out_strides, void *stream);
+
+/*
  * Spatial-row anchor scheme (Section 3.3; "Inference stage" of Section 3.4:
  * heads flagged as spatially repetitive run dense attention on a reduced query
  * set and broadcast the result).

@@ -19,6 +19,10 @@ class CalibattError(RuntimeError):
         super().__init__(f"{where}: {strerror(status)} (status {status})")
 
 
+class _CStrides(C.Structure):
+    _fields_ = [("b", C.c_int64), ("h", C.c_int64), ("n", C.c_int64)]
+
+
 class _CPattern(C.Structure):
     _fields_ = [
         ("H", C.c_int32), ("N", C.c_int32), ("block_q", C.c_int32), ("block_k", C.c_int32),
@@ -97,6 +101,12 @@ def load_library():
     lib.calibatt_merge_intervals.argtypes = [u8p, C.c_int64, C.c_int, C.c_double, u8p, i32p]
     lib.calibatt_share_timesteps.restype = C.c_int
     lib.calibatt_share_timesteps.argtypes = [u8p, C.c_int, C.c_int64, C.c_double, i32p, u8p, i32p]
+    lib.calibatt_sparse_attn_fwd_strided.restype = C.c_int
+    lib.calibatt_sparse_attn_fwd_strided.argtypes = [
+        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+        C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+        C.POINTER(_CPattern), C.c_float, C.POINTER(_CStrides), C.POINTER(_CStrides), C.c_void_p,
+    ]
     lib.calibatt_strerror.restype = C.c_char_p
     lib.calibatt_strerror.argtypes = [C.c_int]
     lib.calibatt_version.restype = C.c_int
@@ -262,22 +272,34 @@ class DevicePattern:
 
 def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
                     block_q: Optional[int] = None, block_k: Optional[int] = None, stream=None):
-    """calibatt_sparse_attn_fwd on torch bf16 CUDA tensors [B, H, N, D]."""
+    """calibatt_sparse_attn_fwd on torch bf16 CUDA tensors of logical shape [B, H, N, D].  The tensors
+    may be strided views (e.g. ``x.transpose(1, 2)`` of a [B, N, H, D] tensor, or slices of a fused
+    [B, N, 3, H, D] projection) as long as D is contiguous and q, k, v share their strides; then the
+    strided entry point is used."""
     import torch
 
     lib = load_library()
     for t in (q, k, v, out):
-        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
-            raise ValueError("q, k, v, out must be contiguous bf16 CUDA tensors [B, H, N, D]")
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.dim() == 4 and t.stride(3) == 1):
+            raise ValueError("q, k, v, out must be bf16 CUDA tensors [B, H, N, D] with contiguous D")
         if t.shape != q.shape:
             raise ValueError("q, k, v, out must have the same shape")
+    if not (q.stride() == k.stride() == v.stride()):
+        raise ValueError("q, k, v must share their strides")
     B, H, N, D = q.shape
     bq = pattern.host.block_q if block_q is None else block_q
     bk = pattern.host.block_k if block_k is None else block_k
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
-    st = lib.calibatt_sparse_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                                      B, H, N, D, bq, bk, C.byref(pattern.c), float(scale), C.c_void_p(stream))
+    if all(t.is_contiguous() for t in (q, k, v, out)):
+        st = lib.calibatt_sparse_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                          B, H, N, D, bq, bk, C.byref(pattern.c), float(scale), C.c_void_p(stream))
+    else:
+        si = _CStrides(q.stride(0), q.stride(1), q.stride(2))
+        so = _CStrides(out.stride(0), out.stride(1), out.stride(2))
+        st = lib.calibatt_sparse_attn_fwd_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                                  B, H, N, D, bq, bk, C.byref(pattern.c), float(scale),
+                                                  C.byref(si), C.byref(so), C.c_void_p(stream))
     if st != 0:
         raise CalibattError(st, "calibatt_sparse_attn_fwd")
     return out

@@ -20,11 +20,17 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 #define LDS_PTR(T) __attribute__((address_space(3))) T *
 
+// Element strides of a [B][H][N][D] tensor whose D axis is contiguous.
+struct Strides {
+  long long b, h, n;
+};
+
 struct FwdDims {
   int B, H, N, nbq, nbk, n_work;
   float scale_log2e;
   int n_groups;                         // segments of the work list (1, or one per XCD)
   int group_ptr[CALIBATT_GROUPS + 1];   // segment g = work[group_ptr[g] .. group_ptr[g+1])
+  Strides in, out;                      // q, k, v share `in`; only the two-workgroup kernel reads these
 };
 
 template <int N_OUTSTANDING>
@@ -93,20 +99,21 @@ struct TileLoader {
   static constexpr bool INVARIANT = (RPI % (FOR_V ? 4 : 16)) == 0;
   static_assert(ROWS % RPI == 0, "tile must split evenly over the workgroup");
 
-  static __device__ __forceinline__ uint32_t lane_offset(int tid, int it) {
+  // row_bytes: distance between consecutive rows of the matrix in memory (D * 2 when rows are packed)
+  static __device__ __forceinline__ uint32_t lane_offset(int tid, int it, uint32_t row_bytes = D * 2) {
     const int row = it * RPI + tid / CH;
     const int cs = tid % CH;
     const int c = cs ^ (FOR_V ? v_swz<D>(row) : k_swz<D>(row));
-    return (tid / CH) * (D * 2) + c * 16;
+    return (tid / CH) * row_bytes + c * 16;
   }
 
   // lds_wave_off: LDS byte address of the tile + 1024 * wave index (wave-uniform)
   static __device__ __forceinline__ void issue(const u32x4 rsrc, int row0, uint32_t lds_wave_off, int tid,
-                                               uint32_t lane_off0) {
+                                               uint32_t lane_off0, uint32_t row_bytes = D * 2) {
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
-      const uint32_t voff = INVARIANT ? lane_off0 : lane_offset(tid, it);
-      const uint32_t soff = (uint32_t)(row0 + it * RPI) * (D * 2);
+      const uint32_t voff = INVARIANT ? lane_off0 : lane_offset(tid, it, row_bytes);
+      const uint32_t soff = (uint32_t)(row0 + it * RPI) * row_bytes;
       dma_16B_per_lane(rsrc, voff, soff, lds_wave_off + it * NT * 16);
     }
   }

@@ -57,20 +57,22 @@ struct RowBlock {
   char *lds, *ldsK, *ldsV;
   int tid, lane, wave, l32, g;
   uint32_t k_lane_off, v_lane_off, ldsK_wave, ldsV_wave;
+  uint32_t kv_row_bytes;  // distance between consecutive K (and V) rows in memory
   uint32_t k_addr0, v_addr[DB];
   bf16x8 qreg[DS];  // Q^T as MFMA B operand: lane (query l32, half g) holds d = 16 s + 8 g + [0,8)
   f32x16 o[DB];
   float m_run;  // running max of scaled (log2-domain) logits, shared by lane and lane^32
   float l_run;  // this lane's share of the running row sum
 
-  __device__ __forceinline__ explicit RowBlock(char *lds_) : lds(lds_), ldsK(lds_), ldsV(lds_ + TILE_BYTES) {
+  __device__ __forceinline__ explicit RowBlock(char *lds_, uint32_t kv_row_bytes_ = ROWB)
+      : lds(lds_), ldsK(lds_), ldsV(lds_ + TILE_BYTES), kv_row_bytes(kv_row_bytes_) {
     tid = threadIdx.x;
     lane = tid & 63;
     wave = tid >> 6;
     l32 = lane & 31;
     g = lane >> 5;
-    k_lane_off = LoadK::lane_offset(tid, 0);
-    v_lane_off = LoadV::lane_offset(tid, 0);
+    k_lane_off = LoadK::lane_offset(tid, 0, kv_row_bytes);
+    v_lane_off = LoadV::lane_offset(tid, 0, kv_row_bytes);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     ldsK_wave = lds_base + wave_u * 1024;
@@ -93,12 +95,16 @@ struct RowBlock {
   // Query row this lane owns within the block.
   __device__ __forceinline__ int row_in_block() const { return wave * 32 + l32; }
 
-  __device__ __forceinline__ void issue_k(const u32x4 &Kres, int c) const { LoadK::issue(Kres, c * BK, ldsK_wave, tid, k_lane_off); }
+  __device__ __forceinline__ void issue_k(const u32x4 &Kres, int c) const {
+    LoadK::issue(Kres, c * BK, ldsK_wave, tid, k_lane_off, kv_row_bytes);
+  }
   // K tile c into the LDS window at byte offset `buf_off` (a multiple of TILE_BYTES)
   __device__ __forceinline__ void issue_k_at(const u32x4 &Kres, int c, uint32_t buf_off) const {
-    LoadK::issue(Kres, c * BK, ldsK_wave + buf_off, tid, k_lane_off);
+    LoadK::issue(Kres, c * BK, ldsK_wave + buf_off, tid, k_lane_off, kv_row_bytes);
   }
-  __device__ __forceinline__ void issue_v(const u32x4 &Vres, int c) const { LoadV::issue(Vres, c * BK, ldsV_wave, tid, v_lane_off); }
+  __device__ __forceinline__ void issue_v(const u32x4 &Vres, int c) const {
+    LoadV::issue(Vres, c * BK, ldsV_wave, tid, v_lane_off, kv_row_bytes);
+  }
 
   // Start a row block: `qrow_ptr` points at the D bf16 of this lane's query row.
   __device__ __forceinline__ void begin(const uint16_t *qrow_ptr) {
@@ -302,7 +308,7 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   // LDS_BYTES + 64 (work-item mailbox) [+ IV_COLS * 4 (column list) if IV]
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   int *const cols = reinterpret_cast<int *>(lds + LDS_BYTES + 64);
-  RB rb(lds);
+  RB rb(lds, (uint32_t)p.in.n * 2);
   const int tid = rb.tid;
   const int lane = rb.lane;
   const int N = p.N;
@@ -344,9 +350,11 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   const int id = work[item];
   const int h = id / p.nbq;
   const int r = id - h * p.nbq;
-  const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
-  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
-  const u32x4 Vres = head_rsrc(gv + head_off, (uint32_t)N * ROWB);
+  // q, k, v: element (b, h, n, d) at b * in.b + h * in.h + n * in.n + d; out likewise with `out`
+  const size_t head_off = (size_t)b * p.in.b + (size_t)h * p.in.h;
+  const uint32_t head_bytes = (uint32_t)(N - 1) * rb.kv_row_bytes + ROWB;  // first byte after the last row
+  const u32x4 Kres = head_rsrc(gk + head_off, head_bytes);
+  const u32x4 Vres = head_rsrc(gv + head_off, head_bytes);
 
   const int cbeg = row_ptr[id];
   const int cend = row_ptr[id + 1];
@@ -380,7 +388,7 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   {
     int qrow = r * BQ + rb.row_in_block();
     qrow = qrow < N ? qrow : N - 1;
-    rb.begin(gq + head_off + (size_t)qrow * D);
+    rb.begin(gq + head_off + (size_t)qrow * p.in.n);
   }
   const float sc = p.scale_log2e;
 
@@ -408,18 +416,18 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   rb.stage_result();
   const int fbeg = fan_ptr[item];
   const int fend = fan_ptr[item + 1];
-  uint16_t *const out_head = gout + head_off;
+  uint16_t *const out_head = gout + (size_t)b * p.out.b + (size_t)h * p.out.h;
   for (int f = fbeg - 1; f < fend; ++f) {
     const int rd = f < fbeg ? r : fan_dst[f];
     const int rows_valid = min(BQ, N - rd * BQ);
-    uint16_t *dst = out_head + (size_t)rd * BQ * D;
+    uint16_t *dst = out_head + (size_t)rd * BQ * p.out.n;
 #pragma unroll 4
     for (int L = tid; L < BQ * CH; L += NT) {
       const int row = L / CH;
       const int cc = L % CH;
       if (row < rows_valid) {
         const u32x4 val = *reinterpret_cast<const u32x4 *>(lds + row * OST + cc * 16);
-        *reinterpret_cast<u32x4 *>(dst + (size_t)row * D + cc * 8) = val;
+        *reinterpret_cast<u32x4 *>(dst + (size_t)row * p.out.n + cc * 8) = val;
       }
     }
   }

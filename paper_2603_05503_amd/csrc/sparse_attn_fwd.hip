@@ -98,7 +98,10 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
     if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
     return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
   }
-  const Variant variant = wanted_variant();
+  // the alternative kernels read packed [B][H][N][D] tensors only
+  const bool packed = p.in.n == D && p.in.h == (long long)p.N * D && p.in.b == (long long)p.H * p.N * D &&
+                      p.out.n == D && p.out.h == (long long)p.N * D && p.out.b == (long long)p.H * p.N * D;
+  const Variant variant = packed ? wanted_variant() : Variant::TwoWg;
   if constexpr (BQ <= BK) {
     if (variant == Variant::PingPong) {
       static DevInfo info[64];
@@ -226,9 +229,33 @@ extern "C" int calibatt_anchor_attn_fwd(const void *q, const void *k, const void
   return launch_anchor<64>(a, head_ids, q_index, dst_ptr, dst_idx, p, s);
 }
 
+namespace {
+bool strides_ok(const calibatt_strides &t, int B, int H, int N, int D) {
+  if (t.n < D || t.b < 0 || t.h < 0 || (t.n % 8) || (t.h % 8) || (t.b % 8)) return false;
+  // the kernels address one head's rows with 32-bit byte offsets
+  if ((unsigned long long)(N - 1) * (unsigned long long)t.n * 2 + (unsigned long long)D * 2 > 0xffffffffULL) return false;
+  (void)B;
+  (void)H;
+  return true;
+}
+}  // namespace
+
 extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void *v, void *out, int B,
                                         int H, int N, int D, int block_q, int block_k,
                                         const calibatt_pattern *pattern, float scale, void *stream) {
+  if (B <= 0 || H <= 0 || N <= 0 || D <= 0) return q && k && v && out && pattern ? CALIBATT_ERR_SHAPE : CALIBATT_ERR_NULL;
+  const calibatt_strides packed = {(int64_t)H * N * D, (int64_t)N * D, (int64_t)D};
+  if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
+  return calibatt_sparse_attn_fwd_strided(q, k, v, out, B, H, N, D, block_q, block_k, pattern, scale, &packed, &packed,
+                                          stream);
+}
+
+extern "C" int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, const void *v, void *out, int B,
+                                                int H, int N, int D, int block_q, int block_k,
+                                                const calibatt_pattern *pattern, float scale,
+                                                const calibatt_strides *in_strides,
+                                                const calibatt_strides *out_strides, void *stream) {
+  if (!in_strides || !out_strides) return CALIBATT_ERR_NULL;
   if (!q || !k || !v || !out || !pattern) return CALIBATT_ERR_NULL;
   if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || block_q <= 0 || block_k <= 0) return CALIBATT_ERR_SHAPE;
   if (!(D == 64 || D == 128) || !(block_q == 64 || block_q == 128) || !(block_k == 64 || block_k == 128))
@@ -250,7 +277,8 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
       (pattern->nnz > 0 && !pattern->col_idx && !intervals) || (pattern->n_repeat > 0 && !pattern->fan_dst))
     return CALIBATT_ERR_NULL;
   if (intervals && nbk > 65535) return CALIBATT_ERR_UNSUPPORTED;
-  if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
+  if (!strides_ok(*in_strides, B, H, N, D) || !strides_ok(*out_strides, B, H, N, D)) return CALIBATT_ERR_SHAPE;
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return CALIBATT_ERR_SHAPE;
 
   FwdPtrs a;
   a.q = (const uint16_t *)q;
@@ -275,6 +303,8 @@ extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void
   p.scale_log2e = scale * 1.4426950408889634f;
   p.n_groups = pattern->n_groups;
   for (int g = 0; g <= CALIBATT_GROUPS; ++g) p.group_ptr[g] = pattern->group_ptr[g];
+  p.in = Strides{in_strides->b, in_strides->h, in_strides->n};
+  p.out = Strides{out_strides->b, out_strides->h, out_strides->n};
   hipStream_t s = (hipStream_t)stream;
 #define CALIBATT_CASE(d, bq, bk) \
   if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, pattern->max_row, s);
