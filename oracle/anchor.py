@@ -25,6 +25,14 @@ What is computed for a head flagged as spatially repetitive:
 
 Nothing is tiled or reordered: the anchor queries' logits against all keys are
 materialised and pushed through a max-subtracted softmax.
+
+Detection (Section 3.3, second paragraph): the spatial similarity score of a
+head is the cosine similarity between the flattened attention rows of a spatial
+row, P^(f,i) = flatten(P[I^(f,i), :]) (Ws tokens x N keys), and those of its
+nearest anchor row, averaged over frames f and spatial rows i.  Reading: the
+average runs over every spatial row, anchors included (their similarity is 1);
+a head is flagged when the score, further averaged over prompts by the caller,
+exceeds the threshold gamma.
 """
 from __future__ import annotations
 
@@ -119,4 +127,31 @@ def anchor_attention(
             for lo in range(0, q_index.size, chunk):
                 a[lo : lo + chunk] = dense_rows(qf[lo : lo + chunk], kf, vf, scale)
             out[b, i] = a[src]
+    return out
+
+
+def spatial_similarity(q_bits: np.ndarray, k_bits: np.ndarray, F: int, Hs: int, Ws: int, k: int, scale: float) -> np.ndarray:
+    """Score s[b, h] of every head (Section 3.3): mean over frames and spatial
+    rows of cos(P^(f,i), P^(f,a(i))).  Materialises P of the video tokens: small
+    inputs only."""
+    B, H, N, D = q_bits.shape
+    n_video = F * Hs * Ws
+    a = anchor_rows(Hs, k)
+    near = nearest_anchor(Hs, k)
+    out = np.zeros((B, H), dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            qf = bf16_bits_to_f64(q_bits[b, h, :n_video])
+            kf = bf16_bits_to_f64(k_bits[b, h])
+            s = scale * (qf @ kf.T)
+            s = s - s.max(axis=1, keepdims=True)
+            p = np.exp(s)
+            p = p / p.sum(axis=1, keepdims=True)           # Eq. 1, [n_video, N]
+            p = p.reshape(F, Hs, Ws * N)                    # P^(f,i) flattened
+            total = 0.0
+            for f in range(F):
+                for i in range(Hs):
+                    u, w = p[f, i], p[f, int(a[near[i]])]
+                    total += float(u @ w) / (np.sqrt(float(u @ u)) * np.sqrt(float(w @ w)))
+            out[b, h] = total / (F * Hs)
     return out

@@ -181,6 +181,82 @@ def test_chunking_changes_nothing():
 
 
 # ---------------------------------------------------------------------------
+# spatial similarity score (detection of repetitive heads)
+# ---------------------------------------------------------------------------
+def _score_brute(q, k, F, Hs, Ws, kk, scale):
+    """Scalar loops over every (frame, row): flattened probability vectors built entry by entry."""
+    N, D = len(k), len(k[0])
+    centres = [((2 * j + 1) * Hs) // (2 * kk) for j in range(kk)]
+
+    def probs(t):
+        logits = [scale * sum(q[t][d] * k[j][d] for d in range(D)) for j in range(N)]
+        m = max(logits)
+        e = [math.exp(x - m) for x in logits]
+        z = sum(e)
+        return [x / z for x in e]
+
+    total = 0.0
+    for f in range(F):
+        for i in range(Hs):
+            a = min(centres, key=lambda c: (abs(c - i), c))
+            u, w = [], []
+            for x in range(Ws):
+                u += probs((f * Hs + i) * Ws + x)
+                w += probs((f * Hs + a) * Ws + x)
+            dot = sum(p1 * p2 for p1, p2 in zip(u, w))
+            total += dot / math.sqrt(sum(p * p for p in u) * sum(p * p for p in w))
+    return total / (F * Hs)
+
+
+@pytest.mark.parametrize("F,Hs,Ws,k,extra", [(2, 3, 2, 1, 0), (1, 5, 2, 2, 3), (2, 4, 1, 3, 1)])
+def test_score_brute_force(F, Hs, Ws, k, extra):
+    rng = np.random.default_rng(300 + F + Hs + Ws + k)
+    N, D = F * Hs * Ws + extra, 4
+    q, kk = _bits(rng, (1, 2, N, D), 1.5), _bits(rng, (1, 2, N, D), 1.5)
+    got = A.spatial_similarity(q, kk, F, Hs, Ws, k, 0.6)
+    for h in range(2):
+        want = _score_brute(_f64(q[0, h]).tolist(), _f64(kk[0, h]).tolist(), F, Hs, Ws, k, 0.6)
+        assert abs(got[0, h] - want) < 1e-12
+
+
+def test_score_special_cases():
+    rng = np.random.default_rng(11)
+    F, Hs, Ws, D = 2, 6, 3, 8
+    N = F * Hs * Ws + 4
+    k = _bits(rng, (1, 1, N, D), 2.0)
+    q = _bits(rng, (1, 1, N, D), 2.0)
+    # every row an anchor: each row is compared with itself
+    np.testing.assert_allclose(A.spatial_similarity(q, k, F, Hs, Ws, Hs, 0.5), 1.0, rtol=1e-14)
+    # queries that do not depend on the spatial row: identical attention rows, score 1 for any k
+    base = _bits(rng, (1, 1, F, 1, Ws, D))
+    qv = np.broadcast_to(base, (1, 1, F, Hs, Ws, D)).reshape(1, 1, F * Hs * Ws, D)
+    q_same = np.concatenate([qv, q[:, :, F * Hs * Ws :]], axis=2)
+    for kk in (1, 2, 3):
+        np.testing.assert_allclose(A.spatial_similarity(q_same, k, F, Hs, Ws, kk, 0.5), 1.0, rtol=1e-14)
+    # generic queries: strictly between 0 and 1, and more anchors never lower the score here
+    s1 = A.spatial_similarity(q, k, F, Hs, Ws, 1, 0.5)[0, 0]
+    s3 = A.spatial_similarity(q, k, F, Hs, Ws, 3, 0.5)[0, 0]
+    assert 0 < s1 < s3 < 1
+
+
+def test_score_one_hot_attention_counts_matching_rows():
+    """Huge logits make every query attend to exactly one key: a row's cosine
+    with its anchor is the fraction of columns that pick the same key."""
+    F, Hs, Ws, D = 1, 4, 2, 4
+    N = F * Hs * Ws
+    kf = np.zeros((N, D), np.float32)
+    for j in range(4):
+        kf[j, j] = 1.0  # keys 0..3 are the unit vectors; the rest are zero
+    qf = np.zeros((N, D), np.float32)
+    pick = {(0, 0): 0, (0, 1): 1, (1, 0): 0, (1, 1): 1, (2, 0): 0, (2, 1): 3, (3, 0): 2, (3, 1): 3}
+    for (i, x), j in pick.items():
+        qf[i * Ws + x, j] = 200.0
+    q, k = f32_to_bf16_bits(qf[None, None]), f32_to_bf16_bits(kf[None, None])
+    # one anchor (row 2, picks keys 0 and 3): rows 0, 1 share column 0 only -> 1/2; row 2 -> 1; row 3 shares column 1 -> 1/2
+    np.testing.assert_allclose(A.spatial_similarity(q, k, F, Hs, Ws, 1, 1.0), (0.5 + 0.5 + 1 + 0.5) / 4, rtol=1e-12)
+
+
+# ---------------------------------------------------------------------------
 # mutants: plausible mistakes planted in a copy of the oracle must be caught
 # ---------------------------------------------------------------------------
 def _run_pins(mod):
