@@ -255,6 +255,38 @@ int calibatt_anchor_attn_fwd(const void *q, const void *k, const void *v, void *
                              int n_q, float scale, void *stream);
 
 /*
+ * Detection of spatially repetitive heads (Section 3.3): the spatial
+ * similarity score of a head is the cosine similarity between the attention
+ * rows of a spatial row of tokens and those of its nearest anchor row (same
+ * frame; both flattened over column and key), averaged over frames and spatial
+ * rows - every row counts, anchors included (their similarity is 1).  A head
+ * is flagged when the score, averaged over calibration prompts by the caller,
+ * exceeds the threshold gamma (0.87 in the paper, with k = 5).
+ *
+ * calibatt_anchor_partner (host): partner[t] = the token of t's nearest anchor
+ * row at the same frame and column, for the F*Hs*Ws video tokens (anchor
+ * positions and ties as in calibatt_anchor_map).  Errors: NULL, SHAPE.
+ *
+ * calibatt_spatial_similarity: score[b][h] for every head, the N x N attention
+ * map never stored.
+ *   q, k       DEVICE, bf16, contiguous [B][H][N][D]; read only.
+ *   partner    DEVICE int32 [n_tok]: token compared with token t (clamped to
+ *              [0, N)); tokens t < n_tok are the ones that have a spatial
+ *              position, in rows of row_len consecutive tokens.
+ *   workspace  DEVICE fp32 [B][H][n_tok][3]: per token the three sums of
+ *              products of probabilities (with the partner, with itself, the
+ *              partner with itself); overwritten.
+ *   score      DEVICE fp32 [B][H].  Same bits on every run.
+ *   stream     hipStream_t (NULL = default stream).  The call only enqueues work.
+ * Supported: D in {64, 128}.  Errors: NULL, SHAPE (a non-positive dimension,
+ * n_tok > N, n_tok not a multiple of row_len), UNSUPPORTED, LAUNCH.
+ */
+int calibatt_anchor_partner(int F, int Hs, int Ws, int k, int32_t *partner);
+int calibatt_spatial_similarity(const void *q, const void *k, int B, int H, int N, int D,
+                                const int32_t *partner, int n_tok, int row_len, float scale,
+                                float *workspace, float *score, void *stream);
+
+/*
  * Calibration steps that turn attention maps into a block mask (Section 3.2).
  * They run offline, once per (timestep, layer, head) and calibration prompt;
  * the energy kernel is the one part that touches N x N work.

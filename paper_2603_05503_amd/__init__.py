@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     HostPattern,
     anchor_attn_fwd,
     anchor_map,
+    anchor_partner,
     block_energy,
     compile_pattern,
     encode_intervals,
@@ -24,6 +25,7 @@ from .binding import (  # noqa: F401
     select_blocks,
     share_timesteps,
     sparse_attn_fwd,
+    spatial_similarity,
     strerror,
     version,
     vote_masks,

@@ -107,6 +107,12 @@ def load_library():
         C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
         C.POINTER(_CPattern), C.c_float, C.POINTER(_CStrides), C.POINTER(_CStrides), C.c_void_p,
     ]
+    lib.calibatt_anchor_partner.restype = C.c_int
+    lib.calibatt_anchor_partner.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, i32p]
+    lib.calibatt_spatial_similarity.restype = C.c_int
+    lib.calibatt_spatial_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p,
+                                                C.c_void_p]
     lib.calibatt_strerror.restype = C.c_char_p
     lib.calibatt_strerror.argtypes = [C.c_int]
     lib.calibatt_version.restype = C.c_int
@@ -486,3 +492,43 @@ def share_timesteps(masks, tau: float):
     if st != 0:
         raise CalibattError(st, "calibatt_share_timesteps")
     return cluster, shared[: n_clusters.value].copy()
+
+
+def anchor_partner(F, Hs, Ws, k) -> np.ndarray:
+    """calibatt_anchor_partner: int32 [F*Hs*Ws], the token each video token is compared with."""
+    lib = load_library()
+    if min(F, Hs, Ws) <= 0:
+        raise CalibattError(-2, "calibatt_anchor_partner")
+    partner = np.empty(F * Hs * Ws, np.int32)
+    st = lib.calibatt_anchor_partner(F, Hs, Ws, k, _ptr(partner, C.c_int32))
+    if st != 0:
+        raise CalibattError(st, "calibatt_anchor_partner")
+    return partner
+
+
+def spatial_similarity(q, k, partner, row_len: int, scale: float, workspace=None, stream=None):
+    """calibatt_spatial_similarity on torch bf16 CUDA tensors [B, H, N, D]; ``partner`` is an int32
+    CUDA tensor [n_tok].  Returns the fp32 CUDA tensor [B, H] of scores."""
+    import torch
+
+    lib = load_library()
+    for t in (q, k):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
+            raise ValueError("q, k must be contiguous bf16 CUDA tensors [B, H, N, D]")
+    if q.shape != k.shape:
+        raise ValueError("q and k must have the same shape")
+    if not (partner.is_cuda and partner.dtype == torch.int32 and partner.is_contiguous() and partner.dim() == 1):
+        raise ValueError("partner must be a contiguous 1-d int32 CUDA tensor")
+    B, H, N, D = q.shape
+    n_tok = partner.numel()
+    if workspace is None:
+        workspace = torch.empty((B, H, max(n_tok, 1), 3), dtype=torch.float32, device=q.device)
+    score = torch.empty((B, H), dtype=torch.float32, device=q.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = lib.calibatt_spatial_similarity(q.data_ptr(), k.data_ptr(), B, H, N, D, partner.data_ptr(), n_tok,
+                                         int(row_len), float(scale), workspace.data_ptr(), score.data_ptr(),
+                                         C.c_void_p(stream))
+    if st != 0:
+        raise CalibattError(st, "calibatt_spatial_similarity")
+    return score

@@ -45,3 +45,18 @@ extern "C" int calibatt_anchor_map(int N, int F, int Hs, int Ws, int k, int32_t 
   dst_ptr[i] = pos;
   return CALIBATT_OK;
 }
+
+extern "C" int calibatt_anchor_partner(int F, int Hs, int Ws, int k, int32_t *partner) {
+  if (!partner) return CALIBATT_ERR_NULL;
+  if (F <= 0 || Hs <= 0 || Ws <= 0 || k <= 0 || k > Hs) return CALIBATT_ERR_SHAPE;
+  for (int f = 0; f < F; ++f) {
+    int j = 0;  // nearest anchor of row y; moves up once the next anchor is strictly nearer
+    for (int y = 0; y < Hs; ++y) {
+      auto anchor_row = [&](int jj) { return (int)(((int64_t)(2 * jj + 1) * Hs) / (2 * k)); };
+      while (j + 1 < k && anchor_row(j + 1) - y < y - anchor_row(j)) ++j;
+      const int a = anchor_row(j);
+      for (int x = 0; x < Ws; ++x) partner[(f * Hs + y) * Ws + x] = (f * Hs + a) * Ws + x;
+    }
+  }
+  return CALIBATT_OK;
+}

@@ -106,15 +106,20 @@ struct RowBlock {
     LoadV::issue(Vres, c * BK, ldsV_wave, tid, v_lane_off, kv_row_bytes);
   }
 
-  // Start a row block: `qrow_ptr` points at the D bf16 of this lane's query row.
-  __device__ __forceinline__ void begin(const uint16_t *qrow_ptr) {
+  // A query row as MFMA B operand: `qrow_ptr` points at the D bf16 of this lane's row.
+  __device__ __forceinline__ void load_q(const uint16_t *qrow_ptr, bf16x8 (&dst)[DS]) const {
     const uint16_t *qp = qrow_ptr + 8 * g;
 #pragma unroll
-    for (int s = 0; s < DS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+    for (int s = 0; s < DS; ++s) dst[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
     // touch the registers here so that the compiler's wait for these loads sits
     // in front of the tile loop and not inside it
 #pragma unroll
-    for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qreg[s]));
+    for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(dst[s]));
+  }
+
+  // Start a row block: `qrow_ptr` points at the D bf16 of this lane's query row.
+  __device__ __forceinline__ void begin(const uint16_t *qrow_ptr) {
+    load_q(qrow_ptr, qreg);
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -125,7 +130,9 @@ struct RowBlock {
 
   // S^T = K Q^T for the K tile at byte offset `buf_off` of the LDS window:
   // s_acc[kb][v] = dot(key 32 kb + 16 (v >> 3) + 8 g + (v & 7), query l32), unscaled.
-  __device__ __forceinline__ void scores(uint32_t buf_off, f32x16 (&s_acc)[KB]) const {
+  __device__ __forceinline__ void scores(uint32_t buf_off, f32x16 (&s_acc)[KB]) const { scores(buf_off, s_acc, qreg); }
+  // The same against an explicit query operand (see load_q).
+  __device__ __forceinline__ void scores(uint32_t buf_off, f32x16 (&s_acc)[KB], const bf16x8 (&q)[DS]) const {
     const char *const kbuf = ldsK + buf_off;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
@@ -147,7 +154,7 @@ struct RowBlock {
       }
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
-        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][kb], qreg[s], s_acc[kb], 0, 0, 0);
+        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][kb], q[s], s_acc[kb], 0, 0, 0);
     }
     __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab 0
 #pragma unroll

@@ -9,6 +9,7 @@
 #include "attn_kernel_2wg.h"
 #include "attn_kernel_anchor.h"
 #include "attn_kernel_energy.h"
+#include "attn_kernel_similarity.h"
 #include "attn_kernel_pipe.h"
 #include "attn_kernel_pp.h"
 #include "calibatt.h"
@@ -167,7 +168,46 @@ int launch_energy(const uint16_t *q, const uint16_t *k, float *energy, const Ene
   return launch_kernel(kernel, (unsigned)grid, BQ * 2, (int)smem, stream, q, k, energy, p);
 }
 
+template <int D>
+int launch_similarity(const uint16_t *q, const uint16_t *k, const int32_t *partner, float *triples, float *score,
+                      const SimilarityDims &p, hipStream_t stream) {
+  const long long units = (long long)p.B * p.H * p.nbq;
+  const long long grid = SIM_XCDS * ((units + SIM_XCDS - 1) / SIM_XCDS);
+  if (grid > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
+  constexpr int SMEM = 2 * RowBlock<D, SIM_BQ, SIM_BK>::TILE_BYTES;
+  auto kernel = pair_similarity_kernel<D>;
+  static DevInfo info[64];
+  int slots = 0;
+  if (int st = prepare(kernel, SIM_BQ * 2, SMEM, info, slots)) return st;
+  if (int st = launch_kernel(kernel, (unsigned)grid, SIM_BQ * 2, SMEM, stream, q, k, partner, triples, p)) return st;
+  return launch_kernel(similarity_reduce_kernel, (unsigned)(p.B * p.H), 64, 0, stream, (const float *)triples, score,
+                       p.n_tok, p.row_len);
+}
+
 }  // namespace
+
+extern "C" int calibatt_spatial_similarity(const void *q, const void *k, int B, int H, int N, int D,
+                                           const int32_t *partner, int n_tok, int row_len, float scale,
+                                           float *workspace, float *score, void *stream) {
+  if (!q || !k || !partner || !workspace || !score) return CALIBATT_ERR_NULL;
+  if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || n_tok <= 0 || row_len <= 0 || n_tok > N || n_tok % row_len)
+    return CALIBATT_ERR_SHAPE;
+  if (!(D == 64 || D == 128)) return CALIBATT_ERR_UNSUPPORTED;
+  if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
+  SimilarityDims p;
+  p.B = B;
+  p.H = H;
+  p.N = N;
+  p.n_tok = n_tok;
+  p.nbq = (n_tok + SIM_BQ - 1) / SIM_BQ;
+  p.nbk = (N + SIM_BK - 1) / SIM_BK;
+  p.row_len = row_len;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  hipStream_t s = (hipStream_t)stream;
+  if (D == 128)
+    return launch_similarity<128>((const uint16_t *)q, (const uint16_t *)k, partner, workspace, score, p, s);
+  return launch_similarity<64>((const uint16_t *)q, (const uint16_t *)k, partner, workspace, score, p, s);
+}
 
 extern "C" int calibatt_block_energy(const void *q, const void *k, float *energy, int B, int H, int N, int D,
                                      int block_q, int block_k, float scale, void *stream) {

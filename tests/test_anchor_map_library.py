@@ -77,3 +77,25 @@ def test_attn_argument_errors_need_no_gpu():
     assert f(one, one, one, one, 1, 1, 8, 64, one, 1, one, one, one, 1, 1.0, None) == -2  # out aliases q
     assert f(one, one, one, C.c_void_p(32), 1, 1, 8, 96, one, 1, one, one, one, 1, 1.0, None) == -3
     assert f(one, one, one, C.c_void_p(32), 1, 1, 8, 64, None, 0, None, None, None, 0, 1.0, None) == 0  # no-op
+
+
+@pytest.mark.parametrize("F,Hs,Ws,k", [(2, 3, 2, 1), (1, 6, 1, 2), (3, 7, 3, 3), (21, 30, 52, 5), (21, 30, 52, 1), (2, 9, 4, 9)])
+def test_partner_matches_oracle(F, Hs, Ws, k):
+    q_index, src = anchor_token_maps(F * Hs * Ws, F, Hs, Ws, k)
+    got = pkg.anchor_partner(F, Hs, Ws, k)
+    assert got.dtype == np.int32 and np.array_equal(got, q_index[src])
+
+
+def test_partner_errors():
+    lib = pkg.load_library()
+    assert lib.calibatt_anchor_partner(1, 2, 2, 1, None) == -1
+    buf = np.zeros(8, np.int32)
+    p = buf.ctypes.data_as(C.POINTER(C.c_int32))
+    assert lib.calibatt_anchor_partner(0, 2, 2, 1, p) == -2
+    assert lib.calibatt_anchor_partner(1, 2, 2, 3, p) == -2
+    one = C.c_void_p(16)
+    f = lib.calibatt_spatial_similarity
+    assert f(None, one, 1, 1, 8, 64, one, 8, 2, 1.0, one, one, None) == -1
+    assert f(one, one, 1, 1, 8, 64, one, 9, 3, 1.0, one, one, None) == -2   # more tokens than N
+    assert f(one, one, 1, 1, 8, 64, one, 8, 3, 1.0, one, one, None) == -2   # rows do not divide
+    assert f(one, one, 1, 1, 8, 96, one, 8, 2, 1.0, one, one, None) == -3

@@ -12,7 +12,7 @@ import math
 import numpy as np
 import pytest
 
-from oracle import block_energy, block_energy_rows, select_blocks, sparse_attention
+from oracle import block_energy, block_energy_rows, select_blocks, sparse_attention, spatial_similarity
 from tests.parity_utils import bits_to_f64, from_dev, to_dev
 from workloads import f32_to_bf16_bits
 
@@ -135,3 +135,56 @@ def test_calibration_chain(lib):
     rel = np.linalg.norm(got - dense) / np.linalg.norm(dense)
     print(f"density {own.mean():.3f}, rel. L2 distance to dense attention {rel:.3f}", flush=True)
     assert rel < 0.5
+
+
+# ---------------------------------------------------------------------------
+# spatial similarity score (Section 3.3).  Tolerance: the score is a mean of
+# ratios of sums of products of probabilities, each with the relative error of
+# the energies (<= ~5e-4); 2e-3 absolute on a value in [0, 1].
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("B,H,F,Hs,Ws,k,extra,D,gain,scale", [
+    (1, 2, 2, 5, 20, 2, 0, 128, 1.0, None),      # 200 tokens: one ragged block
+    (2, 3, 3, 7, 20, 3, 37, 128, 2.0, None),     # tokens without a position, ragged keys, batch 2
+    (1, 2, 4, 6, 33, 1, 0, 64, 2.0, None),       # head dim 64, one anchor
+    (1, 1, 3, 9, 40, 9, 5, 128, 2.0, None),      # every row an anchor: score 1
+    (1, 2, 2, 8, 16, 3, 0, 64, 3.0, -0.2),       # negative scale
+])
+def test_spatial_similarity_parity(lib, B, H, F, Hs, Ws, k, extra, D, gain, scale):
+    import torch
+
+    print(f"similarity B={B} H={H} F={F} Hs={Hs} Ws={Ws} k={k} extra={extra} D={D}", flush=True)
+    N = F * Hs * Ws + extra
+    q, kk = _qk(71 + F + Hs + Ws + k, B, H, N, D, gain)
+    scale = 1 / math.sqrt(D) if scale is None else scale
+    partner = torch.from_numpy(lib.anchor_partner(F, Hs, Ws, k)).cuda()
+    tq, tk = to_dev(q), to_dev(kk)
+    got = lib.spatial_similarity(tq, tk, partner, Ws, scale)
+    torch.cuda.synchronize()
+    want = spatial_similarity(q, kk, F, Hs, Ws, k, scale)
+    np.testing.assert_allclose(got.cpu().numpy().astype(np.float64), want, rtol=0, atol=2e-3)
+    if k == Hs:
+        np.testing.assert_allclose(got.cpu().numpy(), 1.0, rtol=0, atol=1e-5)
+    again = lib.spatial_similarity(tq, tk, partner, Ws, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(got, again)
+
+
+def test_spatial_similarity_separates_repetitive_heads(lib):
+    """Head 0: queries independent of the spatial row (the premise of Section 3.3)
+    -> score 1; head 1: independent random queries -> a low score.  The paper's
+    threshold 0.87 separates them."""
+    import torch
+
+    print("similarity separation", flush=True)
+    F, Hs, Ws, D, k = 3, 10, 26, 128, 5
+    N = F * Hs * Ws
+    rng = np.random.default_rng(81)
+    base = (2.0 * rng.standard_normal((F, 1, Ws, D))).astype(np.float32)
+    q0 = np.broadcast_to(base, (F, Hs, Ws, D)).reshape(N, D)
+    q1 = (2.0 * rng.standard_normal((N, D))).astype(np.float32)
+    q = f32_to_bf16_bits(np.stack([q0, q1])[None])
+    kk = f32_to_bf16_bits((2.0 * rng.standard_normal((1, 2, N, D))).astype(np.float32))
+    partner = torch.from_numpy(lib.anchor_partner(F, Hs, Ws, k)).cuda()
+    s = lib.spatial_similarity(to_dev(q), to_dev(kk), partner, Ws, 1 / math.sqrt(D)).cpu().numpy()[0]
+    print("scores", s, flush=True)
+    assert s[0] > 0.999 and s[1] < 0.87
