@@ -46,7 +46,7 @@ def parse_args():
     ap.add_argument("--intervals", action="store_true",
                     help="hand the pattern over as runs of consecutive key blocks instead of block indices")
     ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
-    ap.add_argument("--no-energy", action="store_true", help="skip the block-energy (calibration) kernel")
+    ap.add_argument("--no-energy", action="store_true", help="skip the calibration kernels (block energy, spatial similarity)")
     ap.add_argument("--anchor-k", type=int, nargs="*", default=None,
                     help="anchor rows per frame to time (default: the k of the paper's table)")
     return ap.parse_args()
@@ -125,6 +125,32 @@ def energy_leg(pkg, torch, q, k, wl, steps):
     row_sums = E.sum(dim=-1)
     return {"ms": t, "tflops": flops / (t * 1e-3) / 1e12,
             "max_row_sum_error": float((row_sums - 1).abs().max())}
+
+
+def similarity_leg(pkg, torch, q, k, wl, steps, anchors=5):
+    """Spatial similarity score (Section 3.3) of all heads for 5 anchor rows per frame: kernel
+    milliseconds by HIP events; flops = four QK^T passes over the video tokens = 8 n_tok N D per head."""
+    F, Hs, Ws = wl.geometry
+    if anchors > Hs:
+        return None
+    partner = torch.from_numpy(pkg.anchor_partner(F, Hs, Ws, anchors)).cuda()
+    n_tok = partner.numel()
+    work = torch.empty((wl.B, wl.H, n_tok, 3), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    score = pkg.spatial_similarity(q, k, partner, Ws, wl.scale, workspace=work)
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        pkg.spatial_similarity(q, k, partner, Ws, wl.scale, workspace=work)
+        b.record(stream)
+        torch.cuda.synchronize()
+        ms.append(a.elapsed_time(b))
+    t = sum(ms) / len(ms)
+    flops = 8.0 * n_tok * wl.N * wl.D * wl.H * wl.B
+    return {"anchors": anchors, "ms": t, "tflops": flops / (t * 1e-3) / 1e12,
+            "score_min": float(score.min()), "score_max": float(score.max())}
 
 
 def cpu_oracle_baseline(wl, n_blocks):
@@ -286,6 +312,8 @@ def main():
         result["anchor_rows"] = anchor_table(pkg, torch, q, k, v, out, wl, max(3, args.steps // 4), args.anchor_k)
     if not args.no_energy:
         result["block_energy"] = energy_leg(pkg, torch, q, k, wl, max(3, args.steps // 4))
+        if getattr(wl, "geometry", None) is not None:
+            result["spatial_similarity"] = similarity_leg(pkg, torch, q, k, wl, max(3, args.steps // 4))
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_oracle_baseline(wl, args.cpu_blocks)
     print(json.dumps(result))
