@@ -43,6 +43,11 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one elementwise kernel that reads and writes 1 GiB each (reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="full step sweep: one distinct pattern per (layer, timestep), all compiled and uploaded "
+                         "up front, then layers x timesteps launches timed")
+    ap.add_argument("--sweep-layers", type=int, default=40)
+    ap.add_argument("--sweep-steps", type=int, default=50)
     ap.add_argument("--intervals", action="store_true",
                     help="hand the pattern over as runs of consecutive key blocks instead of block indices")
     ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
@@ -210,12 +215,100 @@ def profiled_traffic(args):
     return None
 
 
+def _sweep_compile(job):
+    """Worker of the sweep's pattern build (CPU only): generate and compile one (layer, step) pattern."""
+    layer, step, heads, order = job
+    import paper_2603_05503_amd as pkg
+    from workloads import CONFIGS, sweep_pattern
+
+    cfg = CONFIGS["wan480"]
+    mask, repeat, stats = sweep_pattern(layer, step, heads=heads)
+    N, blk = cfg["geom"].n_tokens, cfg["block"]
+    hp = pkg.compile_pattern(mask, repeat, heads, N, blk, blk, order)
+    return layer, step, hp, stats["density"], stats["repeat_frac"]
+
+
+def sweep(args):
+    """Wan-480p shape, one seeded pattern per (layer, timestep) with density ~ U(0.1, 0.6) and repeat
+    fraction ~ U(0, 0.3); patterns are built by a pool of CPU workers BEFORE the GPU is touched,
+    uploaded once, then every timestep runs its layers back to back."""
+    import multiprocessing as mp
+
+    heads = args.heads or 40
+    jobs = [(l, t, heads, args.order) for t in range(args.sweep_steps) for l in range(args.sweep_layers)]
+    t0 = time.perf_counter()
+    with mp.get_context("fork").Pool(min(16, os.cpu_count() or 1)) as pool:
+        built = pool.map(_sweep_compile, jobs, chunksize=4)
+    build_s = time.perf_counter() - t0
+
+    import torch
+
+    import paper_2603_05503_amd as pkg
+    from tests.parity_utils import to_dev
+    from workloads import make_workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    wl = make_workload("wan480", heads=heads)
+    q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
+    out = torch.empty_like(q)
+    t0 = time.perf_counter()
+    patterns = {(l, t): hp.to_device(persistent=not args.no_persistent, intervals=args.intervals)
+                for l, t, hp, _, _ in built}
+    torch.cuda.synchronize()
+    upload_s = time.perf_counter() - t0
+    index_bytes = sum(dp.index_bytes for dp in patterns.values())
+    nnz = sum(hp.nnz for _, _, hp, _, _ in built)
+    tile_flops = 4.0 * wl.block_q * wl.block_k * wl.D
+
+    stream = torch.cuda.current_stream()
+    for l in range(min(args.sweep_layers, 3)):  # warm-up
+        pkg.sparse_attn_fwd(q, k, v, out, patterns[(l, 0)], wl.scale)
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.sweep_steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.sweep_steps)]
+    t0 = time.perf_counter()
+    for t in range(args.sweep_steps):
+        starts[t].record(stream)
+        for l in range(args.sweep_layers):
+            pkg.sparse_attn_fwd(q, k, v, out, patterns[(l, t)], wl.scale)
+        stops[t].record(stream)
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    per_step = sorted(a.elapsed_time(b) for a, b in zip(starts, stops))
+    launches = args.sweep_layers * args.sweep_steps
+    flops = nnz * wl.B * tile_flops
+    dens = [d for *_, d, _ in built]
+    value = flops / wall_s / 1e12
+    print(json.dumps({
+        "metric": "computed-block bf16 TFLOP/s (% MFMA peak); speedup vs dense @ Wan 480p shape",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.sweep_steps, "warmup": 1,
+        "ms_per_step": wall_s * 1e3 / args.sweep_steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"full step sweep: Wan-480p shape B={wl.B} H={wl.H} N={wl.N} D={wl.D}, "
+                               f"{args.sweep_layers} layers x {args.sweep_steps} timesteps, one pattern per (layer, timestep)",
+                   "launches": launches, "kept_blocks_total": int(nnz),
+                   "density_min": min(dens), "density_mean": sum(dens) / len(dens), "density_max": max(dens),
+                   "pattern_form": "intervals" if args.intervals else "indices",
+                   "pattern_index_bytes_total": int(index_bytes),
+                   "pattern_build_s_cpu_pool": build_s, "pattern_upload_s": upload_s},
+        "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "total_attention_s": wall_s,
+        "ms_per_launch_mean": wall_s * 1e3 / launches,
+        "per_timestep_ms": {"min": per_step[0], "median": per_step[len(per_step) // 2], "max": per_step[-1]},
+    }))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (heads would shard across GPUs "
               "without any exchange, see DESIGN.md)", file=sys.stderr)
         sys.exit(2)
+    if args.sweep:
+        return sweep(args)
     import numpy as np
     import torch
 

@@ -73,3 +73,34 @@ def test_fullsize_sampled_parity(lib, name, density):
     print(f"{name}: {len(items)} blocks, max_abs {worst:.3e}, mean_abs {total / n:.3e}, rel_l2 {np.sqrt(num / den):.3e}", flush=True)
     assert worst <= MAX_ABS and total / n <= MEAN_ABS
     assert np.sqrt(num / den) < 2e-2
+
+
+def test_step_sweep_patterns(lib):
+    """A few (layer, timestep) patterns of the full step sweep, 4 heads each, compiled up front and
+    run back to back on the same q, k, v: sampled blocks of every launch against the oracle."""
+    import torch
+    from workloads import sweep_pattern
+
+    print("step sweep", flush=True)
+    wl = make_workload("wan480", heads=4)
+    q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
+    cases = [(0, 0), (3, 7), (39, 49)]
+    built = []
+    for layer, step in cases:
+        mask, repeat, _ = sweep_pattern(layer, step, heads=4)
+        hp = lib.compile_pattern(mask, repeat, 4, wl.N, wl.block_q, wl.block_k, 3)
+        built.append((mask, repeat, hp.to_device(intervals=(step % 2 == 1))))
+    outs = [torch.empty_like(q) for _ in cases]
+    for (mask, repeat, dp), out in zip(built, outs):
+        lib.sparse_attn_fwd(q, k, v, out, dp, wl.scale)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(7)
+    for (mask, repeat, dp), out in zip(built, outs):
+        got = from_dev(out)
+        assert_repeats_bitwise(got, repeat, wl.block_q, wl.N)
+        live = [(h, r) for h in range(4) for r in range(wl.nbq) if repeat[h, r] < 0]
+        items = [(0, *live[i]) for i in rng.choice(len(live), 6, replace=False)] + [(0, 1, wl.nbq - 1)]
+        want = sparse_attention_blocks(wl.q, wl.k, wl.v, mask, repeat, wl.scale, wl.block_q, wl.block_k, items)
+        for (b, h, r), w in zip(items, want):
+            g = bits_to_f64(got[b, h, r * wl.block_q : r * wl.block_q + w.shape[0]])
+            assert np.abs(g - w).max() <= MAX_ABS and np.abs(g - w).mean() <= MEAN_ABS, (h, r)
