@@ -87,6 +87,11 @@ typedef struct calibatt_pattern {
    * non-NULL the forward reads them and never touches col_idx, which may then be NULL. */
   const int32_t *iv_ptr;     /* [H*nbq + 1] offsets into iv */
   const uint32_t *iv;        /* interval words, see calibatt_encode_intervals */
+  /* Optional: the pattern covers a subset of the tensor's heads.  NULL = pattern head h is tensor
+   * head h (and pattern H must equal the tensor's H); else DEVICE int32 [H of the pattern], the
+   * tensor head each pattern head reads and writes (entries outside the tensor's heads are
+   * skipped; heads no entry names are left untouched).  calibatt_compile_pattern sets NULL. */
+  const int32_t *head_map;
 } calibatt_pattern;
 
 /*

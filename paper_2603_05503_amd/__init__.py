@@ -30,3 +30,4 @@ from .binding import (  # noqa: F401
     version,
     vote_masks,
 )
+from .pipeline import CalibAttention, CalibrationResult, Calibrator  # noqa: F401,E402

@@ -36,6 +36,7 @@ class _CPattern(C.Structure):
         ("n_groups", C.c_int32),
         ("group_ptr", C.c_int32 * 9),
         ("iv_ptr", C.c_void_p), ("iv", C.c_void_p),
+        ("head_map", C.c_void_p),
     ]
 
 
@@ -185,9 +186,10 @@ class HostPattern:
     n_groups: int = 1
     group_ptr: Optional[np.ndarray] = None
 
-    def to_device(self, device="cuda", persistent=True, intervals=False) -> "DevicePattern":
-        """``intervals=True`` uploads the interval form of the kept-block lists instead of col_idx."""
-        return DevicePattern(self, device, persistent, intervals)
+    def to_device(self, device="cuda", persistent=True, intervals=False, head_map=None) -> "DevicePattern":
+        """``intervals=True`` uploads the interval form of the kept-block lists instead of col_idx;
+        ``head_map`` (one tensor head per pattern head) makes the pattern act on a subset of heads."""
+        return DevicePattern(self, device, persistent, intervals, head_map)
 
     def encode_intervals(self):
         """(iv_ptr int32 [rows + 1], iv uint32 words) via calibatt_encode_intervals."""
@@ -230,7 +232,7 @@ class DevicePattern:
 
     _NAMES = ("row_ptr", "col_idx", "repeat_src", "work", "fan_ptr", "fan_dst")
 
-    def __init__(self, hp: HostPattern, device="cuda", persistent=True, intervals=False):
+    def __init__(self, hp: HostPattern, device="cuda", persistent=True, intervals=False, head_map=None):
         import torch
 
         self.host = hp
@@ -256,6 +258,14 @@ class DevicePattern:
         else:
             c.iv_ptr = None
             c.iv = None
+        if head_map is not None:
+            hm = np.ascontiguousarray(head_map, dtype=np.int32).reshape(-1)
+            if hm.size != hp.H:
+                raise ValueError(f"head_map has {hm.size} entries, the pattern has {hp.H} heads")
+            self.tensors["head_map"] = torch.from_numpy(hm).to(device)
+            c.head_map = self.tensors["head_map"].data_ptr()
+        else:
+            c.head_map = None
         # int32[16] workspace of the persistent-workgroup scheduler (kept zero between calls)
         self.counter = torch.zeros(16, dtype=torch.int32, device=device) if persistent else None
         c.work_counter = self.counter.data_ptr() if persistent else None

@@ -308,7 +308,8 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
     const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
     uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
-    int32_t *counter, const FwdDims p, const int32_t *__restrict__ iv_ptr, const uint32_t *__restrict__ iv) {
+    int32_t *counter, const FwdDims p, const int32_t *__restrict__ iv_ptr, const uint32_t *__restrict__ iv,
+    const int32_t *__restrict__ head_map) {
   using RB = RowBlock<D, BQ, BK>;
   constexpr int NT = RB::NT, CH = RB::CH, ROWB = RB::ROWB, OST = RB::OST, LDS_BYTES = RB::LDS_BYTES;
 
@@ -357,8 +358,13 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   const int id = work[item];
   const int h = id / p.nbq;
   const int r = id - h * p.nbq;
+  // h is the head of the pattern; the tensors' head may differ (pattern over a subset of heads).
+  // An entry outside the tensor's heads is treated as head 0 for the reads and writes nothing.
+  const int h_raw = head_map ? head_map[h] : h;
+  const bool head_ok = (unsigned)h_raw < (unsigned)p.H;
+  const int ht = head_ok ? h_raw : 0;
   // q, k, v: element (b, h, n, d) at b * in.b + h * in.h + n * in.n + d; out likewise with `out`
-  const size_t head_off = (size_t)b * p.in.b + (size_t)h * p.in.h;
+  const size_t head_off = (size_t)b * p.in.b + (size_t)ht * p.in.h;
   const uint32_t head_bytes = (uint32_t)(N - 1) * rb.kv_row_bytes + ROWB;  // first byte after the last row
   const u32x4 Kres = head_rsrc(gk + head_off, head_bytes);
   const u32x4 Vres = head_rsrc(gv + head_off, head_bytes);
@@ -423,8 +429,8 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   rb.stage_result();
   const int fbeg = fan_ptr[item];
   const int fend = fan_ptr[item + 1];
-  uint16_t *const out_head = gout + (size_t)b * p.out.b + (size_t)h * p.out.h;
-  for (int f = fbeg - 1; f < fend; ++f) {
+  uint16_t *const out_head = gout + (size_t)b * p.out.b + (size_t)ht * p.out.h;
+  for (int f = fbeg - 1; head_ok && f < fend; ++f) {
     const int rd = f < fbeg ? r : fan_dst[f];
     const int rows_valid = min(BQ, N - rd * BQ);
     uint16_t *dst = out_head + (size_t)rd * BQ * p.out.n;

@@ -228,6 +228,7 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
   out->work_counter = nullptr;
   out->iv_ptr = nullptr;
   out->iv = nullptr;
+  out->head_map = nullptr;
   out->n_groups = order == CALIBATT_ORDER_XCD_HEADS ? CALIBATT_GROUPS : 1;
   for (int g = 0; g <= CALIBATT_GROUPS; ++g) out->group_ptr[g] = group_ptr[g];
   return CALIBATT_OK;

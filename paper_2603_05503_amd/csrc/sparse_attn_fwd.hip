@@ -24,6 +24,7 @@ struct FwdPtrs {
   int32_t *counter;
   const int32_t *iv_ptr;  // interval form of the kept-block lists, or NULL
   const uint32_t *iv;
+  const int32_t *head_map;  // tensor head of each pattern head, or NULL
 };
 
 // Per-device launch facts, looked up once per kernel and device.
@@ -69,7 +70,7 @@ int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, c
   if (counter && items > slots) grid = slots; else counter = nullptr;
   if constexpr (TAKES_IV)
     return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
-                         a.work, a.fan_ptr, a.fan_dst, counter, p, a.iv_ptr, a.iv);
+                         a.work, a.fan_ptr, a.fan_dst, counter, p, a.iv_ptr, a.iv, a.head_map);
   else
     return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
                          a.work, a.fan_ptr, a.fan_dst, counter, p);
@@ -102,7 +103,7 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
   // the alternative kernels read packed [B][H][N][D] tensors only
   const bool packed = p.in.n == D && p.in.h == (long long)p.N * D && p.in.b == (long long)p.H * p.N * D &&
                       p.out.n == D && p.out.h == (long long)p.N * D && p.out.b == (long long)p.H * p.N * D;
-  const Variant variant = packed ? wanted_variant() : Variant::TwoWg;
+  const Variant variant = packed && !a.head_map ? wanted_variant() : Variant::TwoWg;
   if constexpr (BQ <= BK) {
     if (variant == Variant::PingPong) {
       static DevInfo info[64];
@@ -302,9 +303,9 @@ extern "C" int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, co
     return CALIBATT_ERR_UNSUPPORTED;
   if (out == q || out == k || out == v) return CALIBATT_ERR_SHAPE;
   const int nbq = (N + block_q - 1) / block_q, nbk = (N + block_k - 1) / block_k;
-  if (pattern->H != H || pattern->N != N || pattern->block_q != block_q || pattern->block_k != block_k ||
+  if ((pattern->head_map ? pattern->H <= 0 : pattern->H != H) || pattern->N != N || pattern->block_q != block_q || pattern->block_k != block_k ||
       pattern->nbq != nbq || pattern->nbk != nbk || pattern->n_work < 0 || pattern->n_repeat < 0 ||
-      (int64_t)pattern->n_work + pattern->n_repeat != (int64_t)H * nbq)
+      (int64_t)pattern->n_work + pattern->n_repeat != (int64_t)pattern->H * nbq)
     return CALIBATT_ERR_PATTERN_MISMATCH;
   if (pattern->n_groups != 1 && pattern->n_groups != CALIBATT_GROUPS) return CALIBATT_ERR_PATTERN_MISMATCH;
   if (pattern->group_ptr[0] != 0 || pattern->group_ptr[pattern->n_groups] != pattern->n_work)
@@ -333,6 +334,7 @@ extern "C" int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, co
   a.counter = pattern->work_counter;
   a.iv_ptr = intervals ? pattern->iv_ptr : nullptr;
   a.iv = intervals ? pattern->iv : nullptr;
+  a.head_map = pattern->head_map;
   FwdDims p;
   p.B = B;
   p.H = H;

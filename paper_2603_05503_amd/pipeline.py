@@ -1,0 +1,128 @@
+"""Calibration and inference stages wired together (paper, Section 3.4) on top of
+the C ABI.  Orchestration only: every computation is a library call.
+
+``Calibrator`` collects, per (timestep, layer) key and over calibration prompts,
+the per-prompt block masks (Section 3.2: block energy, selection at eps(t)) and
+the spatial similarity scores of the heads (Section 3.3); ``finalize`` votes the
+masks (Eq. 8-9) and flags the heads whose mean score exceeds gamma.
+
+``CalibAttention`` is the dictionary that stays on the GPU at inference: per key
+a compiled pattern over the heads that are not flagged (interval form by
+default) and the list of flagged heads, which go through the anchor-row path.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, Hashable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import binding as _b
+
+
+@dataclass
+class CalibrationResult:
+    mask: np.ndarray              # uint8 [H, nbq, nbk], 1 = kept
+    repetitive_heads: List[int]   # heads that take the anchor-row path
+    scores: Optional[np.ndarray]  # mean spatial similarity per head, or None
+    n_prompts: int
+
+
+class Calibrator:
+    def __init__(self, H: int, N: int, D: int, block_q: int = 128, block_k: int = 128,
+                 geometry: Optional[Tuple[int, int, int]] = None, anchors: int = 5,
+                 rho: float = 0.5, gamma: float = 0.87):
+        self.H, self.N, self.D = H, N, D
+        self.block_q, self.block_k = block_q, block_k
+        self.geometry, self.anchors, self.rho, self.gamma = geometry, anchors, rho, gamma
+        self._masks: Dict[Hashable, List[np.ndarray]] = {}
+        self._scores: Dict[Hashable, List[np.ndarray]] = {}
+        self._partner = None
+
+    def observe(self, key: Hashable, q, k, eps: float, scale: float) -> None:
+        """One dense forward's q, k ([B, H, N, D] bf16 CUDA tensors; every batch element counts as a
+        prompt) at the step/layer ``key``, with the energy threshold ``eps`` of that step."""
+        import torch
+
+        energy = _b.block_energy(q, k, self.block_q, self.block_k, scale)
+        masks = _b.select_blocks(energy.cpu().numpy(), eps)  # [B, H, nbq, nbk]
+        self._masks.setdefault(key, []).extend(masks[b] for b in range(masks.shape[0]))
+        if self.geometry is not None:
+            F, Hs, Ws = self.geometry
+            if self._partner is None:
+                self._partner = torch.from_numpy(_b.anchor_partner(F, Hs, Ws, self.anchors)).to(q.device)
+            score = _b.spatial_similarity(q, k, self._partner, Ws, scale).cpu().numpy()
+            self._scores.setdefault(key, []).extend(score[b] for b in range(score.shape[0]))
+
+    def finalize(self, merge_percentile: Optional[float] = None) -> Dict[Hashable, CalibrationResult]:
+        out = {}
+        for key, masks in self._masks.items():
+            mask = _b.vote_masks(np.stack(masks), self.rho)
+            if merge_percentile is not None:
+                mask, _ = _b.merge_intervals(mask, merge_percentile)
+            scores, flagged = None, []
+            if key in self._scores:
+                scores = np.stack(self._scores[key]).astype(np.float64).mean(axis=0)  # average over prompts
+                flagged = [h for h in range(self.H) if scores[h] > self.gamma]
+            out[key] = CalibrationResult(mask=mask, repetitive_heads=flagged, scores=scores, n_prompts=len(masks))
+        return out
+
+
+@dataclass
+class _Entry:
+    pattern: Optional[_b.DevicePattern]
+    head_ids: Optional[object]  # int32 CUDA tensor of the flagged heads, or None
+    kept_blocks: int = 0
+    sparse_heads: List[int] = field(default_factory=list)
+
+
+class CalibAttention:
+    def __init__(self, H: int, N: int, D: int, block_q: int = 128, block_k: int = 128,
+                 geometry: Optional[Tuple[int, int, int]] = None, anchors: int = 5,
+                 intervals: bool = True, order: int = 3, device: str = "cuda"):
+        self.H, self.N, self.D = H, N, D
+        self.block_q, self.block_k = block_q, block_k
+        self.intervals, self.order, self.device = intervals, order, device
+        self.entries: Dict[Hashable, _Entry] = {}
+        self.amap = None
+        if geometry is not None:
+            F, Hs, Ws = geometry
+            self.amap = _b.anchor_map(N, F, Hs, Ws, anchors).to_device(device)
+
+    def add(self, key: Hashable, mask, repetitive_heads: Sequence[int] = (), repeat=None) -> None:
+        """Compile and upload the pattern of ``key``.  ``mask`` [H, nbq, nbk]; ``repetitive_heads`` take
+        the anchor-row path (needs a geometry); ``repeat`` is the optional block-level repeat map."""
+        import torch
+
+        flagged = sorted(set(int(h) for h in repetitive_heads))
+        if flagged and self.amap is None:
+            raise ValueError("repetitive heads need the token geometry")
+        sparse = [h for h in range(self.H) if h not in flagged]
+        m = np.asarray(mask)
+        pattern, kept = None, 0
+        if sparse:
+            rep = None if repeat is None else np.asarray(repeat)[sparse]
+            hp = _b.compile_pattern(m[sparse], rep, len(sparse), self.N, self.block_q, self.block_k, self.order)
+            head_map = None if len(sparse) == self.H else sparse
+            pattern = hp.to_device(self.device, intervals=self.intervals, head_map=head_map)
+            kept = hp.nnz
+        head_ids = torch.tensor(flagged, dtype=torch.int32, device=self.device) if flagged else None
+        self.entries[key] = _Entry(pattern, head_ids, kept, sparse)
+
+    def add_calibrated(self, results: Dict[Hashable, CalibrationResult]) -> None:
+        for key, res in results.items():
+            self.add(key, res.mask, res.repetitive_heads)
+
+    def __call__(self, q, k, v, out, key: Hashable, scale: float, stream=None):
+        """One attention call of step/layer ``key``: the sparse forward on the heads of the pattern,
+        the anchor-row forward on the flagged heads; together they write every head of ``out``."""
+        e = self.entries[key]
+        if e.pattern is not None:
+            _b.sparse_attn_fwd(q, k, v, out, e.pattern, scale, stream=stream)
+        if e.head_ids is not None:
+            _b.anchor_attn_fwd(q, k, v, out, e.head_ids, self.amap, scale, stream=stream)
+        return out
+
+    @property
+    def index_bytes(self) -> int:
+        return sum(e.pattern.index_bytes for e in self.entries.values() if e.pattern is not None)
