@@ -84,3 +84,36 @@ def test_strided_argument_checks(lib):
     assert call(ok, _CStrides(H * N * D, N * D, 1 << 40)) == -2    # beyond 32-bit byte offsets
     assert call(ok, ok, qp=q.data_ptr() + 2) == -2                 # misaligned pointer
     torch.cuda.synchronize()
+
+
+def test_pattern_over_a_subset_of_heads(lib):
+    """head_map: the pattern's heads act on chosen tensor heads, in any order; heads that no entry
+    names and entries outside the tensor's heads write nothing."""
+    import torch
+
+    print("head map", flush=True)
+    B, H, N, D, blk = 2, 5, 600, 128, 128
+    q, k, v = _qkv(91, B, H, N, D)
+    nb = -(-N // blk)
+    chosen = [3, 0, 7, 4]  # pattern head i acts on tensor head chosen[i]; 7 does not exist
+    mask, repeat = random_mask(92, len(chosen), nb, nb, 0.5, 0.3, keep_diagonal=True, tail_partial=True)
+    hp = lib.compile_pattern(mask, repeat, len(chosen), N, blk, blk, 3)
+    tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
+    for intervals in (False, True):
+        out = torch.empty_like(tq)
+        out.view(torch.int16).fill_(0x7FC1)
+        lib.sparse_attn_fwd(tq, tk, tv, out, hp.to_device(intervals=intervals, head_map=chosen), 0.09)
+        torch.cuda.synchronize()
+        got = from_dev(out)
+        for i, h in enumerate(chosen):
+            if h >= H:
+                continue
+            want = sparse_attention(q[:, h : h + 1], k[:, h : h + 1], v[:, h : h + 1], mask[i : i + 1],
+                                    repeat[i : i + 1], 0.09, blk, blk)
+            assert_parity(got[:, h : h + 1], want, f"tensor head {h}")
+        for h in (1, 2):
+            assert (got[:, h] == 0x7FC1).all()
+    # without a head map the head counts must agree
+    with pytest.raises(lib.CalibattError) as e:
+        lib.sparse_attn_fwd(tq, tk, tv, torch.empty_like(tq), hp.to_device(), 0.09)
+    assert e.value.status == -8
