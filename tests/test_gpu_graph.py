@@ -1,0 +1,59 @@
+"""The forward calls under HIP graph capture: the library launches kernels only
+(the persistent scheduler re-arms its own counters, nothing is cleared with a
+memset), so a captured graph must replay to the eager result every time."""
+import math
+
+import numpy as np
+import pytest
+
+from tests.parity_utils import from_dev, to_dev
+from workloads import f32_to_bf16_bits, random_mask
+
+pytestmark = pytest.mark.gpu
+
+
+def test_graph_replays_match_eager(lib):
+    import torch
+
+    print("graph capture", flush=True)
+    B, H, N, D, blk = 4, 8, 4000, 128, 128  # more work items than resident workgroups: persistent launch
+    F, Hs, Ws = 5, 10, 80
+    rng = np.random.default_rng(17)
+    q, k, v = (f32_to_bf16_bits((2.0 * rng.standard_normal((B, H, N, D))).astype(np.float32)) for _ in range(3))
+    nb = -(-N // blk)
+    mask, repeat = random_mask(18, H - 2, nb, nb, 0.3, 0.2, keep_diagonal=True, tail_partial=True)
+    hp = lib.compile_pattern(mask, repeat, H - 2, N, blk, blk, 3)
+    dp = hp.to_device(persistent=True, intervals=True, head_map=list(range(2, H)))
+    assert hp.n_work * B > 512
+    amap = lib.anchor_map(N, F, Hs, Ws, 3).to_device()
+    heads = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
+    scale = 1 / math.sqrt(D)
+
+    def run(out, stream=None):
+        lib.sparse_attn_fwd(tq, tk, tv, out, dp, scale, stream=stream)
+        lib.anchor_attn_fwd(tq, tk, tv, out, heads, amap, scale, stream=stream)
+
+    eager = torch.empty_like(tq)
+    run(eager)  # also the warm-up: kernel attributes are set outside the capture
+    torch.cuda.synchronize()
+    want = from_dev(eager)
+    assert np.isfinite((want.astype(np.uint32) << 16).view(np.float32)).all()
+
+    out = torch.empty_like(tq)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run(out, stream=side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for i in range(4):
+        out.view(torch.int16).fill_(0x7FC1)   # eager work between the replays
+        run(eager)                            # shares the scheduler workspace with the graph: same stream order
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (from_dev(out) == want).all(), f"replay {i}"
+        assert (from_dev(eager) == want).all()
