@@ -8,7 +8,12 @@ heads, wait for it.  Patterns are compiled once before the timed region (the
 paper builds its skip lists offline, Section 3.4); q/k/v/out are resident in
 HBM.  The metric is computed-block bf16 TFLOP/s = kept blocks * 4*bq*bk*D / t.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: the headline metric with its roofline object (MFMA bound,
+achieved by HIP events, traffic from the committed rocprofv3 summary), the dense
+reference run of the same kernel, the clock the GPU sustained, the CPU oracle
+baseline, and side tables for the anchor-row path (the k of the paper's table),
+the block-energy kernel and the spatial similarity kernel.  ``--sweep`` runs the
+full step sweep instead (one pattern per layer and timestep).
 """
 from __future__ import annotations
 
@@ -305,7 +310,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (heads would shard across GPUs "
-              "without any exchange, see DESIGN.md)", file=sys.stderr)
+              "without any exchange)", file=sys.stderr)
         sys.exit(2)
     if args.sweep:
         return sweep(args)
