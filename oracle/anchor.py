@@ -155,3 +155,25 @@ def spatial_similarity(q_bits: np.ndarray, k_bits: np.ndarray, F: int, Hs: int, 
                     total += float(u @ w) / (np.sqrt(float(u @ u)) * np.sqrt(float(w @ w)))
             out[b, h] = total / (F * Hs)
     return out
+
+
+def spatial_similarity_rows(q_bits, k_bits, F: int, Hs: int, Ws: int, k: int, scale: float, items) -> list:
+    """cos(P^(f,i), P^(f,a(i))) of selected spatial rows only: ``items`` holds
+    (b, h, f, i).  Same arithmetic as ``spatial_similarity``, whose score is the
+    mean of these values over all (f, i)."""
+    a = anchor_rows(Hs, k)
+    near = nearest_anchor(Hs, k)
+    out = []
+    for (b, h, f, i) in items:
+        kf = bf16_bits_to_f64(k_bits[b, h])
+
+        def flat_probs(row):
+            t0 = (f * Hs + row) * Ws
+            s = scale * (bf16_bits_to_f64(q_bits[b, h, t0 : t0 + Ws]) @ kf.T)
+            s = s - s.max(axis=1, keepdims=True)
+            p = np.exp(s)
+            return (p / p.sum(axis=1, keepdims=True)).reshape(-1)
+
+        u, w = flat_probs(i), flat_probs(int(a[near[i]]))
+        out.append(float(u @ w) / (np.sqrt(float(u @ u)) * np.sqrt(float(w @ w))))
+    return out

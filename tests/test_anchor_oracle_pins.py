@@ -219,6 +219,17 @@ def test_score_brute_force(F, Hs, Ws, k, extra):
         assert abs(got[0, h] - want) < 1e-12
 
 
+def test_score_is_the_mean_of_its_rows():
+    rng = np.random.default_rng(12)
+    F, Hs, Ws, k, D = 2, 5, 3, 2, 4
+    N = F * Hs * Ws + 2
+    q, kk = _bits(rng, (1, 2, N, D), 1.5), _bits(rng, (1, 2, N, D), 1.5)
+    full = A.spatial_similarity(q, kk, F, Hs, Ws, k, 0.6)
+    for h in range(2):
+        rows = A.spatial_similarity_rows(q, kk, F, Hs, Ws, k, 0.6, [(0, h, f, i) for f in range(F) for i in range(Hs)])
+        assert abs(np.mean(rows) - full[0, h]) < 1e-14
+
+
 def test_score_special_cases():
     rng = np.random.default_rng(11)
     F, Hs, Ws, D = 2, 6, 3, 8

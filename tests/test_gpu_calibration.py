@@ -12,7 +12,7 @@ import math
 import numpy as np
 import pytest
 
-from oracle import block_energy, block_energy_rows, select_blocks, sparse_attention, spatial_similarity
+from oracle import block_energy, block_energy_rows, select_blocks, sparse_attention, spatial_similarity, spatial_similarity_rows
 from tests.parity_utils import bits_to_f64, from_dev, to_dev
 from workloads import f32_to_bf16_bits
 
@@ -188,3 +188,28 @@ def test_spatial_similarity_separates_repetitive_heads(lib):
     s = lib.spatial_similarity(to_dev(q), to_dev(kk), partner, Ws, 1 / math.sqrt(D)).cpu().numpy()[0]
     print("scores", s, flush=True)
     assert s[0] > 0.999 and s[1] < 0.87
+
+
+def test_spatial_similarity_wan480_sampled(lib):
+    """Full Wan-480p geometry (k = 5) on three heads of the bench workload's q, k:
+    the cosines of sampled spatial rows, rebuilt from the kernel's per-token
+    sums, against the oracle; the score equals the mean of all rows' cosines."""
+    import torch
+    from workloads import make_workload
+
+    print("similarity wan480", flush=True)
+    wl = make_workload("wan480", heads=3, qk_gain=1.5)
+    F, Hs, Ws = wl.geometry
+    partner = torch.from_numpy(lib.anchor_partner(F, Hs, Ws, 5)).cuda()
+    n_tok = partner.numel()
+    work = torch.empty((1, 3, n_tok, 3), dtype=torch.float32, device="cuda")
+    score = lib.spatial_similarity(to_dev(wl.q), to_dev(wl.k), partner, Ws, wl.scale, workspace=work)
+    torch.cuda.synchronize()
+    sums = work.cpu().numpy().astype(np.float64).reshape(3, F * Hs, Ws, 3).sum(axis=2)
+    cos = sums[..., 0] / np.sqrt(sums[..., 1] * sums[..., 2])            # [head, frame * row]
+    np.testing.assert_allclose(score.cpu().numpy()[0], cos.mean(axis=1), rtol=0, atol=1e-5)
+    items = [(0, 0, 0, 0), (0, 1, 10, 6), (0, 2, 20, 29), (0, 1, 5, 15), (0, 0, 13, 12)]
+    want = spatial_similarity_rows(wl.q, wl.k, F, Hs, Ws, 5, wl.scale, items)
+    for (b, h, f, i), w in zip(items, want):
+        assert abs(cos[h, f * Hs + i] - w) <= 2e-3, (h, f, i, cos[h, f * Hs + i], w)
+    assert abs(cos[1, 5 * Hs + 15] - 1.0) < 1e-5  # row 15 is an anchor: compared with itself
