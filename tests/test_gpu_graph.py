@@ -57,3 +57,38 @@ def test_graph_replays_match_eager(lib):
         torch.cuda.synchronize()
         assert (from_dev(out) == want).all(), f"replay {i}"
         assert (from_dev(eager) == want).all()
+
+
+def test_calls_on_two_streams_overlap_safely(lib):
+    """No state is shared between calls except the caller's workspaces: two patterns, each with its
+    own workspace, launched on two streams at the same time give the bits of the serial runs."""
+    import torch
+
+    print("two streams", flush=True)
+    B, H, N, D, blk = 2, 16, 3000, 128, 128
+    rng = np.random.default_rng(19)
+    q, k, v = (f32_to_bf16_bits((2.0 * rng.standard_normal((B, H, N, D))).astype(np.float32)) for _ in range(3))
+    nb = -(-N // blk)
+    tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
+    pats = []
+    for seed, dens in ((20, 0.3), (21, 0.6)):
+        mask, repeat = random_mask(seed, H, nb, nb, dens, 0.2, keep_diagonal=True, tail_partial=True)
+        pats.append(lib.compile_pattern(mask, repeat, H, N, blk, blk, 3).to_device(persistent=True, intervals=seed == 21))
+    assert all(dp.host.n_work * B > 512 for dp in pats)
+    serial = []
+    for dp in pats:
+        out = torch.empty_like(tq)
+        lib.sparse_attn_fwd(tq, tk, tv, out, dp, 0.09)
+        torch.cuda.synchronize()
+        serial.append(from_dev(out))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        outs = [torch.empty_like(tq) for _ in pats]
+        for s in streams:
+            s.wait_stream(torch.cuda.current_stream())
+        for dp, out, s in zip(pats, outs, streams):
+            for _ in range(2):  # back-to-back calls on one stream may share a workspace
+                lib.sparse_attn_fwd(tq, tk, tv, out, dp, 0.09, stream=s.cuda_stream)
+        torch.cuda.synchronize()
+        for out, want in zip(outs, serial):
+            assert (from_dev(out) == want).all(), rep
