@@ -27,6 +27,12 @@
 extern "C" {
 #endif
 
+/* Element strides of a [B][H][N][D] tensor whose D axis is contiguous (see
+ * calibatt_sparse_attn_fwd_strided). */
+typedef struct calibatt_strides {
+  int64_t b, h, n; /* in elements */
+} calibatt_strides;
+
 typedef enum calibatt_status {
   CALIBATT_OK = 0,
   CALIBATT_ERR_NULL = -1,             /* a required pointer is NULL */
@@ -190,9 +196,6 @@ int calibatt_sparse_attn_fwd(const void *q, const void *k, const void *v, void *
  * Errors: as calibatt_sparse_attn_fwd; SHAPE also for strides or alignment
  * that break the requirements.
  */
-typedef struct calibatt_strides {
-  int64_t b, h, n; /* in elements */
-} calibatt_strides;
 int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, const void *v, void *out, int B,
                                      int H, int N, int D, int block_q, int block_k,
                                      const calibatt_pattern *pattern, float scale,
@@ -258,6 +261,15 @@ int calibatt_anchor_attn_fwd(const void *q, const void *k, const void *v, void *
                              int N, int D, const int32_t *head_ids, int n_heads,
                              const int32_t *q_index, const int32_t *dst_ptr, const int32_t *dst_idx,
                              int n_q, float scale, void *stream);
+
+/* The same on strided tensors; strides, requirements and errors as in
+ * calibatt_sparse_attn_fwd_strided. */
+int calibatt_anchor_attn_fwd_strided(const void *q, const void *k, const void *v, void *out, int B,
+                                     int H, int N, int D, const int32_t *head_ids, int n_heads,
+                                     const int32_t *q_index, const int32_t *dst_ptr,
+                                     const int32_t *dst_idx, int n_q, float scale,
+                                     const calibatt_strides *in_strides,
+                                     const calibatt_strides *out_strides, void *stream);
 
 /*
  * Detection of spatially repetitive heads (Section 3.3): the spatial

@@ -114,6 +114,9 @@ def load_library():
     lib.calibatt_spatial_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p,
                                                 C.c_void_p]
+    lib.calibatt_anchor_attn_fwd_strided.restype = C.c_int
+    lib.calibatt_anchor_attn_fwd_strided.argtypes = lib.calibatt_anchor_attn_fwd.argtypes[:-1] + [
+        C.POINTER(_CStrides), C.POINTER(_CStrides), C.c_void_p]
     lib.calibatt_strerror.restype = C.c_char_p
     lib.calibatt_strerror.argtypes = [C.c_int]
     lib.calibatt_version.restype = C.c_int
@@ -364,25 +367,33 @@ class DeviceAnchorMap:
 
 
 def anchor_attn_fwd(q, k, v, out, head_ids, amap: DeviceAnchorMap, scale: float, stream=None):
-    """calibatt_anchor_attn_fwd on torch bf16 CUDA tensors [B, H, N, D];
-    ``head_ids`` is an int32 CUDA tensor of the heads to process."""
+    """calibatt_anchor_attn_fwd on torch bf16 CUDA tensors of logical shape [B, H, N, D] (strided views
+    with contiguous D allowed, q, k, v sharing their strides); ``head_ids`` is an int32 CUDA tensor of
+    the heads to process."""
     import torch
 
     lib = load_library()
     for t in (q, k, v, out):
-        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
-            raise ValueError("q, k, v, out must be contiguous bf16 CUDA tensors [B, H, N, D]")
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.dim() == 4 and t.stride(3) == 1):
+            raise ValueError("q, k, v, out must be bf16 CUDA tensors [B, H, N, D] with contiguous D")
         if t.shape != q.shape:
             raise ValueError("q, k, v, out must have the same shape")
+    if not (q.stride() == k.stride() == v.stride()):
+        raise ValueError("q, k, v must share their strides")
     if not (head_ids.is_cuda and head_ids.dtype == torch.int32 and head_ids.is_contiguous() and head_ids.dim() == 1):
         raise ValueError("head_ids must be a contiguous 1-d int32 CUDA tensor")
     B, H, N, D = q.shape
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
-    st = lib.calibatt_anchor_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, D,
-                                      head_ids.data_ptr(), head_ids.numel(), amap.q_index.data_ptr(),
-                                      amap.dst_ptr.data_ptr(), amap.dst_idx.data_ptr(), amap.n_q,
-                                      float(scale), C.c_void_p(stream))
+    args = (q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, D,
+            head_ids.data_ptr(), head_ids.numel(), amap.q_index.data_ptr(),
+            amap.dst_ptr.data_ptr(), amap.dst_idx.data_ptr(), amap.n_q, float(scale))
+    if all(t.is_contiguous() for t in (q, k, v, out)):
+        st = lib.calibatt_anchor_attn_fwd(*args, C.c_void_p(stream))
+    else:
+        si = _CStrides(q.stride(0), q.stride(1), q.stride(2))
+        so = _CStrides(out.stride(0), out.stride(1), out.stride(2))
+        st = lib.calibatt_anchor_attn_fwd_strided(*args, C.byref(si), C.byref(so), C.c_void_p(stream))
     if st != 0:
         raise CalibattError(st, "calibatt_anchor_attn_fwd")
     return out

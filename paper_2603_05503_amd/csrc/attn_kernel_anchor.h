@@ -24,6 +24,7 @@ namespace calibatt_dev {
 struct AnchorDims {
   int B, H, N, n_heads, n_q, nbq, nbk;
   float scale_log2e;
+  Strides in, out;  // element strides of q, k, v (shared) and of out
 };
 
 constexpr int ANCHOR_BQ = 128;
@@ -69,12 +70,13 @@ __global__ __launch_bounds__(ANCHOR_BQ * 2, 2) void anchor_attn_fwd_kernel(
   const int h = head_ids[bh - b * p.n_heads];
   if ((unsigned)h >= (unsigned)p.H) return;
 
-  RB rb(lds);
+  RB rb(lds, (uint32_t)p.in.n * 2);
   const int tid = rb.tid;
   const int N = p.N;
-  const size_t head_off = ((size_t)b * p.H + h) * (size_t)N * D;
-  const u32x4 Kres = head_rsrc(gk + head_off, (uint32_t)N * ROWB);
-  const u32x4 Vres = head_rsrc(gv + head_off, (uint32_t)N * ROWB);
+  const size_t head_off = (size_t)b * p.in.b + (size_t)h * p.in.h;
+  const uint32_t head_bytes = (uint32_t)(N - 1) * rb.kv_row_bytes + ROWB;  // first byte after the last row
+  const u32x4 Kres = head_rsrc(gk + head_off, head_bytes);
+  const u32x4 Vres = head_rsrc(gv + head_off, head_bytes);
   rb.issue_k(Kres, 0);
   rb.issue_v(Vres, 0);
   {
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(ANCHOR_BQ * 2, 2) void anchor_attn_fwd_kernel(
     qi = qi < p.n_q ? qi : p.n_q - 1;
     int tok = q_index[qi];
     tok = tok < 0 ? 0 : (tok < N ? tok : N - 1);
-    rb.begin(gq + head_off + (size_t)tok * D);
+    rb.begin(gq + head_off + (size_t)tok * p.in.n);
   }
   const float sc = p.scale_log2e;
   for (int c = 0; c < p.nbk; ++c) rb.tile(Kres, Vres, c, c + 1 < p.nbk, c + 1, N, p.nbk, sc);
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(ANCHOR_BQ * 2, 2) void anchor_attn_fwd_kernel(
   __syncthreads();
   const int e_begin = s_ptr[0];
   const int e_end = s_ptr[rows_valid];
-  uint16_t *const out_head = gout + head_off;
+  uint16_t *const out_head = gout + (size_t)b * p.out.b + (size_t)h * p.out.h;
   for (int base = e_begin; base < e_end; base += EC) {
     const int n = min(EC, e_end - base);
     for (int j = tid; j < n; j += NT) s_ent[j] = dst_idx[base + j];
@@ -113,7 +115,7 @@ __global__ __launch_bounds__(ANCHOR_BQ * 2, 2) void anchor_attn_fwd_kernel(
       const int tok = s_ent[j];
       if ((unsigned)tok < (unsigned)N) {
         const u32x4 val = *reinterpret_cast<const u32x4 *>(lds + (int)s_row[j] * OST + cc * 16);
-        *reinterpret_cast<u32x4 *>(out_head + (size_t)tok * D + cc * 8) = val;
+        *reinterpret_cast<u32x4 *>(out_head + (size_t)tok * p.out.n + cc * 8) = val;
       }
     }
     __syncthreads();

@@ -129,6 +129,15 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
   return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
 }
 
+bool strides_ok(const calibatt_strides &t, int B, int H, int N, int D) {
+  if (t.n < D || t.b < 0 || t.h < 0 || (t.n % 8) || (t.h % 8) || (t.b % 8)) return false;
+  // the kernels address one head's rows with 32-bit byte offsets
+  if ((unsigned long long)(N - 1) * (unsigned long long)t.n * 2 + (unsigned long long)D * 2 > 0xffffffffULL) return false;
+  (void)B;
+  (void)H;
+  return true;
+}
+
 template <int D>
 int launch_anchor(const FwdPtrs &a, const int32_t *head_ids, const int32_t *q_index, const int32_t *dst_ptr,
                   const int32_t *dst_idx, const AnchorDims &p, hipStream_t stream) {
@@ -244,11 +253,25 @@ extern "C" int calibatt_anchor_attn_fwd(const void *q, const void *k, const void
                                         int N, int D, const int32_t *head_ids, int n_heads,
                                         const int32_t *q_index, const int32_t *dst_ptr,
                                         const int32_t *dst_idx, int n_q, float scale, void *stream) {
-  if (!q || !k || !v || !out) return CALIBATT_ERR_NULL;
+  if (B <= 0 || H <= 0 || N <= 0 || D <= 0) return q && k && v && out ? CALIBATT_ERR_SHAPE : CALIBATT_ERR_NULL;
+  if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
+  const calibatt_strides packed = {(int64_t)H * N * D, (int64_t)N * D, (int64_t)D};
+  return calibatt_anchor_attn_fwd_strided(q, k, v, out, B, H, N, D, head_ids, n_heads, q_index, dst_ptr, dst_idx, n_q,
+                                          scale, &packed, &packed, stream);
+}
+
+extern "C" int calibatt_anchor_attn_fwd_strided(const void *q, const void *k, const void *v, void *out, int B,
+                                                int H, int N, int D, const int32_t *head_ids, int n_heads,
+                                                const int32_t *q_index, const int32_t *dst_ptr,
+                                                const int32_t *dst_idx, int n_q, float scale,
+                                                const calibatt_strides *in_strides,
+                                                const calibatt_strides *out_strides, void *stream) {
+  if (!q || !k || !v || !out || !in_strides || !out_strides) return CALIBATT_ERR_NULL;
   if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || n_heads < 0 || n_q < 0) return CALIBATT_ERR_SHAPE;
   if (!(D == 64 || D == 128)) return CALIBATT_ERR_UNSUPPORTED;
   if (out == q || out == k || out == v) return CALIBATT_ERR_SHAPE;
-  if ((size_t)B * H * N * D > 0x7fffffff00ULL) return CALIBATT_ERR_SHAPE;
+  if (!strides_ok(*in_strides, B, H, N, D) || !strides_ok(*out_strides, B, H, N, D)) return CALIBATT_ERR_SHAPE;
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return CALIBATT_ERR_SHAPE;
   if (n_heads == 0 || n_q == 0) return CALIBATT_OK;
   if (!head_ids || !q_index || !dst_ptr || !dst_idx) return CALIBATT_ERR_NULL;
   FwdPtrs a{};
@@ -265,21 +288,12 @@ extern "C" int calibatt_anchor_attn_fwd(const void *q, const void *k, const void
   p.nbq = (n_q + ANCHOR_BQ - 1) / ANCHOR_BQ;
   p.nbk = (N + ANCHOR_BK - 1) / ANCHOR_BK;
   p.scale_log2e = scale * 1.4426950408889634f;
+  p.in = Strides{in_strides->b, in_strides->h, in_strides->n};
+  p.out = Strides{out_strides->b, out_strides->h, out_strides->n};
   hipStream_t s = (hipStream_t)stream;
   if (D == 128) return launch_anchor<128>(a, head_ids, q_index, dst_ptr, dst_idx, p, s);
   return launch_anchor<64>(a, head_ids, q_index, dst_ptr, dst_idx, p, s);
 }
-
-namespace {
-bool strides_ok(const calibatt_strides &t, int B, int H, int N, int D) {
-  if (t.n < D || t.b < 0 || t.h < 0 || (t.n % 8) || (t.h % 8) || (t.b % 8)) return false;
-  // the kernels address one head's rows with 32-bit byte offsets
-  if ((unsigned long long)(N - 1) * (unsigned long long)t.n * 2 + (unsigned long long)D * 2 > 0xffffffffULL) return false;
-  (void)B;
-  (void)H;
-  return true;
-}
-}  // namespace
 
 extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void *v, void *out, int B,
                                         int H, int N, int D, int block_q, int block_k,

@@ -117,3 +117,28 @@ def test_pattern_over_a_subset_of_heads(lib):
     with pytest.raises(lib.CalibattError) as e:
         lib.sparse_attn_fwd(tq, tk, tv, torch.empty_like(tq), hp.to_device(), 0.09)
     assert e.value.status == -8
+
+
+def test_both_paths_on_a_fused_projection_tensor(lib):
+    """CalibAttention on q, k, v that are slices of one [B, N, 3, H, D] tensor and an output stored as
+    [B, N, H, D]: the sparse forward on three heads and the anchor-row forward on the fourth, no
+    transposed copies; same bits as with packed tensors."""
+    import torch
+
+    print("pipeline strided", flush=True)
+    B, H, D, blk = 1, 4, 128, 128
+    F, Hs, Ws = 3, 6, 40
+    N = F * Hs * Ws
+    q, k, v = _qkv(95, B, H, N, D)
+    nb = -(-N // blk)
+    mask, _ = random_mask(96, H, nb, nb, 0.5, 0.0, keep_diagonal=True, tail_partial=(N % blk) != 0)
+    att = lib.CalibAttention(H, N, D, blk, blk, geometry=(F, Hs, Ws), anchors=2)
+    att.add("key", mask, repetitive_heads=[2])
+    tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
+    packed = torch.empty_like(tq)
+    att(tq, tk, tv, packed, "key", 0.09)
+    fused = torch.stack([t.transpose(1, 2) for t in (tq, tk, tv)], dim=2).contiguous()  # [B, N, 3, H, D]
+    out = torch.full((B, N, H, D), -7.0, dtype=torch.bfloat16, device="cuda")
+    att(*(fused[:, :, i].transpose(1, 2) for i in range(3)), out.transpose(1, 2), "key", 0.09)
+    torch.cuda.synchronize()
+    assert torch.equal(out.transpose(1, 2).contiguous().view(torch.int16), packed.view(torch.int16))
