@@ -345,6 +345,18 @@ int calibatt_select_blocks(const float *energy, int64_t n_rows, int nbk, double 
 int calibatt_vote_masks(const uint8_t *masks, int n_prompts, int64_t n, double rho, uint8_t *out);
 
 /*
+ * The same vote without keeping every prompt's mask: calibatt_vote_accumulate
+ * adds one prompt's mask (n entries, non-zero = kept) to per-block counters
+ * (uint16, zeroed by the caller before the first prompt; at most 65535
+ * prompts), calibatt_vote_finish thresholds them exactly like
+ * calibatt_vote_masks: out[i] = counts[i] / n_prompts >= rho.  HOST buffers.
+ * Errors: NULL, SHAPE (n < 0, n_prompts outside [1, 65535], rho not a number, a
+ * counter that would overflow or exceeds n_prompts).
+ */
+int calibatt_vote_accumulate(const uint8_t *mask, int64_t n, uint16_t *counts);
+int calibatt_vote_finish(const uint16_t *counts, int n_prompts, int64_t n, double rho, uint8_t *out);
+
+/*
  * Energy threshold of diffusion step t of T (Eq. 7): A + (C - A) exp(-k t / T),
  * t = 0 the highest-noise step.  Returns NaN when T <= 0.
  * calibatt_schedule_base_level: the base level A the paper uses in the

@@ -28,6 +28,8 @@ from .binding import (  # noqa: F401
     spatial_similarity,
     strerror,
     version,
+    vote_accumulate,
+    vote_finish,
     vote_masks,
 )
 from .pipeline import CalibAttention, CalibrationResult, Calibrator  # noqa: F401,E402

@@ -91,6 +91,11 @@ def load_library():
     lib.calibatt_select_blocks.argtypes = [C.POINTER(C.c_float), C.c_int64, C.c_int, C.c_double, u8p]
     lib.calibatt_vote_masks.restype = C.c_int
     lib.calibatt_vote_masks.argtypes = [u8p, C.c_int, C.c_int64, C.c_double, u8p]
+    u16p = C.POINTER(C.c_uint16)
+    lib.calibatt_vote_accumulate.restype = C.c_int
+    lib.calibatt_vote_accumulate.argtypes = [u8p, C.c_int64, u16p]
+    lib.calibatt_vote_finish.restype = C.c_int
+    lib.calibatt_vote_finish.argtypes = [u16p, C.c_int, C.c_int64, C.c_double, u8p]
     lib.calibatt_epsilon_schedule.restype = C.c_double
     lib.calibatt_epsilon_schedule.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double]
     lib.calibatt_schedule_base_level.restype = C.c_double
@@ -449,6 +454,28 @@ def vote_masks(masks, rho: float) -> np.ndarray:
     st = lib.calibatt_vote_masks(_ptr(m, C.c_uint8), m.shape[0], out.size, float(rho), _ptr(out, C.c_uint8))
     if st != 0:
         raise CalibattError(st, "calibatt_vote_masks")
+    return out
+
+
+def vote_accumulate(mask, counts: np.ndarray) -> None:
+    """calibatt_vote_accumulate: adds one prompt's mask to the uint16 counters (same shape), in place."""
+    lib = load_library()
+    m = np.ascontiguousarray(mask, dtype=np.uint8)
+    if not (counts.dtype == np.uint16 and counts.flags.c_contiguous and counts.shape == m.shape):
+        raise ValueError("counts must be a C-contiguous uint16 array of the mask's shape")
+    st = lib.calibatt_vote_accumulate(_ptr(m, C.c_uint8), m.size, _ptr(counts, C.c_uint16))
+    if st != 0:
+        raise CalibattError(st, "calibatt_vote_accumulate")
+
+
+def vote_finish(counts: np.ndarray, n_prompts: int, rho: float) -> np.ndarray:
+    """calibatt_vote_finish: uint8 mask of the counters' shape."""
+    lib = load_library()
+    c = np.ascontiguousarray(counts, dtype=np.uint16)
+    out = np.empty(c.shape, np.uint8)
+    st = lib.calibatt_vote_finish(_ptr(c, C.c_uint16), int(n_prompts), c.size, float(rho), _ptr(out, C.c_uint8))
+    if st != 0:
+        raise CalibattError(st, "calibatt_vote_finish")
     return out
 
 

@@ -48,6 +48,24 @@ extern "C" int calibatt_vote_masks(const uint8_t *masks, int n_prompts, int64_t 
   return CALIBATT_OK;
 }
 
+extern "C" int calibatt_vote_accumulate(const uint8_t *mask, int64_t n, uint16_t *counts) {
+  if (!mask || !counts) return CALIBATT_ERR_NULL;
+  if (n < 0) return CALIBATT_ERR_SHAPE;
+  for (int64_t i = 0; i < n; ++i)
+    if (mask[i] != 0 && counts[i] == 65535) return CALIBATT_ERR_SHAPE;  // checked before anything is changed
+  for (int64_t i = 0; i < n; ++i) counts[i] = (uint16_t)(counts[i] + (mask[i] != 0));
+  return CALIBATT_OK;
+}
+
+extern "C" int calibatt_vote_finish(const uint16_t *counts, int n_prompts, int64_t n, double rho, uint8_t *out) {
+  if (!counts || !out) return CALIBATT_ERR_NULL;
+  if (n_prompts <= 0 || n_prompts > 65535 || n < 0 || std::isnan(rho)) return CALIBATT_ERR_SHAPE;
+  for (int64_t i = 0; i < n; ++i)
+    if (counts[i] > n_prompts) return CALIBATT_ERR_SHAPE;
+  for (int64_t i = 0; i < n; ++i) out[i] = ((double)counts[i] / (double)n_prompts >= rho) ? 1 : 0;
+  return CALIBATT_OK;
+}
+
 extern "C" double calibatt_epsilon_schedule(int t, int T, double A, double C, double k) {
   if (T <= 0) return std::numeric_limits<double>::quiet_NaN();
   return A + (C - A) * std::exp(-k * (double)t / (double)T);

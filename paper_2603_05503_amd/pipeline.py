@@ -2,7 +2,8 @@
 the C ABI.  Orchestration only: every computation is a library call.
 
 ``Calibrator`` collects, per (timestep, layer) key and over calibration prompts,
-the per-prompt block masks (Section 3.2: block energy, selection at eps(t)) and
+the votes of the per-prompt block masks (Section 3.2: block energy, selection at
+eps(t); one uint16 counter per block, no mask is kept) and
 the spatial similarity scores of the heads (Section 3.3); ``finalize`` votes the
 masks (Eq. 8-9) and flags the heads whose mean score exceeds gamma.
 
@@ -35,7 +36,8 @@ class Calibrator:
         self.H, self.N, self.D = H, N, D
         self.block_q, self.block_k = block_q, block_k
         self.geometry, self.anchors, self.rho, self.gamma = geometry, anchors, rho, gamma
-        self._masks: Dict[Hashable, List[np.ndarray]] = {}
+        self._counts: Dict[Hashable, np.ndarray] = {}   # uint16 per block: prompts that kept it
+        self._n: Dict[Hashable, int] = {}
         self._scores: Dict[Hashable, List[np.ndarray]] = {}
         self._partner = None
 
@@ -46,7 +48,10 @@ class Calibrator:
 
         energy = _b.block_energy(q, k, self.block_q, self.block_k, scale)
         masks = _b.select_blocks(energy.cpu().numpy(), eps)  # [B, H, nbq, nbk]
-        self._masks.setdefault(key, []).extend(masks[b] for b in range(masks.shape[0]))
+        counts = self._counts.setdefault(key, np.zeros(masks.shape[1:], np.uint16))
+        for b in range(masks.shape[0]):
+            _b.vote_accumulate(masks[b], counts)
+        self._n[key] = self._n.get(key, 0) + masks.shape[0]
         if self.geometry is not None:
             F, Hs, Ws = self.geometry
             if self._partner is None:
@@ -56,15 +61,15 @@ class Calibrator:
 
     def finalize(self, merge_percentile: Optional[float] = None) -> Dict[Hashable, CalibrationResult]:
         out = {}
-        for key, masks in self._masks.items():
-            mask = _b.vote_masks(np.stack(masks), self.rho)
+        for key, counts in self._counts.items():
+            mask = _b.vote_finish(counts, self._n[key], self.rho)
             if merge_percentile is not None:
                 mask, _ = _b.merge_intervals(mask, merge_percentile)
             scores, flagged = None, []
             if key in self._scores:
                 scores = np.stack(self._scores[key]).astype(np.float64).mean(axis=0)  # average over prompts
                 flagged = [h for h in range(self.H) if scores[h] > self.gamma]
-            out[key] = CalibrationResult(mask=mask, repetitive_heads=flagged, scores=scores, n_prompts=len(masks))
+            out[key] = CalibrationResult(mask=mask, repetitive_heads=flagged, scores=scores, n_prompts=self._n[key])
         return out
 
 

@@ -40,6 +40,26 @@ def test_vote_matches_oracle(seed):
         assert np.array_equal(pkg.vote_masks(masks, rho), cal.vote(masks, rho)), rho
 
 
+def test_incremental_vote_equals_the_stacked_vote():
+    rng = np.random.default_rng(7)
+    masks = (rng.random((9, 2, 6, 5)) < 0.5).astype(np.uint8) * rng.integers(1, 255, (9, 2, 6, 5)).astype(np.uint8)
+    counts = np.zeros(masks.shape[1:], np.uint16)
+    for m in masks:
+        pkg.vote_accumulate(m, counts)
+    assert np.array_equal(counts, (masks != 0).sum(axis=0))
+    for rho in (0.0, 0.3, 0.5, 5 / 9, 0.9, 1.0):
+        assert np.array_equal(pkg.vote_finish(counts, 9, rho), cal.vote(masks, rho)), rho
+    lib = pkg.load_library()
+    u8p, u16p = C.POINTER(C.c_uint8), C.POINTER(C.c_uint16)
+    full = np.full(3, 65535, np.uint16)
+    one = np.ones(3, np.uint8)
+    assert lib.calibatt_vote_accumulate(one.ctypes.data_as(u8p), 3, full.ctypes.data_as(u16p)) == -2 and (full == 65535).all()
+    out = np.zeros(3, np.uint8)
+    assert lib.calibatt_vote_finish(full.ctypes.data_as(u16p), 9, 3, 0.5, out.ctypes.data_as(u8p)) == -2  # count > prompts
+    assert lib.calibatt_vote_finish(None, 9, 3, 0.5, out.ctypes.data_as(u8p)) == -1
+    assert lib.calibatt_vote_finish(full.ctypes.data_as(u16p), 0, 3, 0.5, out.ctypes.data_as(u8p)) == -2
+
+
 def test_schedule_matches_oracle_and_paper():
     A = pkg.schedule_base_level(32760)
     assert A == cal.schedule_base_level(32760)
