@@ -175,7 +175,11 @@ struct RowBlock {
     wait_vmem<LOADS_PER_WAVE>();
     __syncthreads();
     f32x16 s_acc[KB];
+    // The matrix phases run at raised priority: when the SIMD's other wavefront (of the co-resident
+    // workgroup) is in its softmax, the matrix pipe's issue slots go to this one first.
+    __builtin_amdgcn_s_setprio(2);
     scores(0, s_acc);
+    __builtin_amdgcn_s_setprio(0);
     __syncthreads();  // every wave is done with the K tile
     if (has_next) issue_k(Kres, c_next);
 
@@ -238,6 +242,7 @@ struct RowBlock {
     // ---- O^T += V^T P^T -----------------------------------------------------
     if (has_next) wait_vmem<LOADS_PER_WAVE>(); else wait_vmem<0>();
     __syncthreads();
+    __builtin_amdgcn_s_setprio(2);
     {
       // 16-key slab j = 2 kb + s2: V^T operands of slab j+1 are read while slab j multiplies
       u32x4 va[2][DB];
@@ -269,6 +274,7 @@ struct RowBlock {
         __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
       }
     }
+    __builtin_amdgcn_s_setprio(0);
     __syncthreads();  // every wave is done with the V tile
     if (has_next) issue_v(Vres, c_next);
   }
