@@ -55,6 +55,8 @@ def parse_args():
     ap.add_argument("--sweep-steps", type=int, default=50)
     ap.add_argument("--intervals", action="store_true",
                     help="hand the pattern over as runs of consecutive key blocks instead of block indices")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the MFMA-only probe (zero vs random operands) that gives the practical ceiling")
     ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
     ap.add_argument("--no-energy", action="store_true", help="skip the calibration kernels (block energy, spatial similarity)")
     ap.add_argument("--anchor-k", type=int, nargs="*", default=None,
@@ -161,6 +163,22 @@ def similarity_leg(pkg, torch, q, k, wl, steps, anchors=5):
     flops = 8.0 * n_tok * wl.N * wl.D * wl.H * wl.B
     return {"anchors": anchors, "ms": t, "tflops": flops / (t * 1e-3) / 1e12,
             "score_min": float(score.min()), "score_max": float(score.max())}
+
+
+def mfma_probe(launches=40):
+    """Runs the stand-alone MFMA-only probe as a child process (it has its own GPU context) and returns
+    its JSON: sustained TFLOP/s and clock of v_mfma_f32_32x32x16_bf16 alone with all-zero and with random
+    N(0,1) operands.  None if the executable is missing or fails."""
+    import subprocess
+
+    exe = os.path.join(ROOT, "paper_2603_05503_amd", "mfma_peak_probe.bin")
+    if not os.path.exists(exe):
+        return None
+    try:
+        res = subprocess.run([exe, str(launches)], capture_output=True, text=True, timeout=120)
+        return json.loads(res.stdout.strip().splitlines()[-1]) if res.returncode == 0 else None
+    except (OSError, ValueError, IndexError, subprocess.TimeoutExpired):
+        return None
 
 
 def cpu_oracle_baseline(wl, n_blocks):
@@ -314,6 +332,7 @@ def main():
         sys.exit(2)
     if args.sweep:
         return sweep(args)
+    probe = None if args.no_mfma_probe else mfma_probe()  # before this process touches the GPU
     import numpy as np
     import torch
 
@@ -406,6 +425,10 @@ def main():
             "traffic": profiled_traffic(args),
         },
     }
+    if probe:
+        # the data-sheet peak assumes 2.4 GHz; with random operands the matrix cores alone are clocked lower
+        probe["achieved_over_random_operand_ceiling"] = achieved / probe["random"]["tflops"]
+        result["mfma_probe"] = probe
     if not args.no_anchor and getattr(wl, "geometry", None) is not None:
         result["anchor_rows"] = anchor_table(pkg, torch, q, k, v, out, wl, max(3, args.steps // 4), args.anchor_k)
     if not args.no_energy:

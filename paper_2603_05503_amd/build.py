@@ -9,6 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libcalibatt.so")
+PROBE_PATH = os.path.join(PKG_DIR, "mfma_peak_probe.bin")  # stand-alone executable, see csrc/mfma_peak_probe.hip
 
 SOURCES = ["compile_pattern.cpp", "anchor_map.cpp", "calibration.cpp", "skiplist.cpp", "sparse_attn_fwd.hip"]
 
@@ -39,6 +40,11 @@ def build(verbose: bool = True, extra_flags=()) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     check_pipelined_kernel(extra_flags)
+    probe = [hipcc(), *[f for f in HIP_FLAGS if f not in ("-fPIC", "-shared")], "-Wno-unused-value",
+             os.path.join(CSRC, "mfma_peak_probe.hip"), "-o", PROBE_PATH]
+    if verbose:
+        print(" ".join(probe), flush=True)
+    subprocess.run(probe, check=True)
     return LIB_PATH
 
 
