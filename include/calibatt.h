@@ -13,6 +13,15 @@
  *      blocks with an online softmax) over the kept blocks only.
  * Heads flagged as spatially repetitive (Section 3.3 at token-row granularity)
  * go through calibatt_anchor_map() / calibatt_anchor_attn_fwd() instead.
+ * Both forwards have a *_strided variant for tensors that are not packed.
+ *
+ * The calibration stage (Section 3.2-3.3) that produces the masks and the
+ * flags: calibatt_block_energy() and calibatt_spatial_similarity() on the GPU,
+ * calibatt_select_blocks(), calibatt_vote_*(), calibatt_epsilon_schedule() on
+ * the host.  Skip-list tools of the supplement (Sections A.2, A.3):
+ * calibatt_encode_intervals() (a compact form of the index lists that the
+ * forward reads directly), calibatt_merge_intervals(),
+ * calibatt_share_timesteps().
  *
  * Plain C, no exceptions cross the boundary, no global state is kept between
  * calls, every buffer is owned by the caller.  All functions return a
