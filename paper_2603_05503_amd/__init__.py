@@ -32,4 +32,4 @@ from .binding import (  # noqa: F401
     vote_finish,
     vote_masks,
 )
-from .pipeline import CalibAttention, CalibrationResult, Calibrator  # noqa: F401,E402
+from .pipeline import CalibAttention, CalibrationResult, Calibrator, load_calibration, save_calibration  # noqa: F401,E402

@@ -73,6 +73,37 @@ class Calibrator:
         return out
 
 
+def save_calibration(path: str, results: Dict[Hashable, CalibrationResult]) -> None:
+    """Writes the calibrated masks and flags to one .npz file (block masks bit-packed).  Keys must be
+    tuples of integers, e.g. (timestep, layer)."""
+    arrays = {}
+    keys = sorted(results)
+    arrays["keys"] = np.array([list(k) for k in keys], dtype=np.int64).reshape(len(keys), -1)
+    for i, key in enumerate(keys):
+        res = results[key]
+        arrays[f"mask_shape_{i}"] = np.array(res.mask.shape, dtype=np.int64)
+        arrays[f"mask_bits_{i}"] = np.packbits(np.asarray(res.mask, dtype=np.uint8).reshape(-1) != 0)
+        arrays[f"heads_{i}"] = np.array(res.repetitive_heads, dtype=np.int32)
+        arrays[f"scores_{i}"] = np.zeros(0) if res.scores is None else np.asarray(res.scores, dtype=np.float64)
+        arrays[f"prompts_{i}"] = np.array([res.n_prompts], dtype=np.int64)
+    np.savez_compressed(path, **arrays)
+
+
+def load_calibration(path: str) -> Dict[Hashable, CalibrationResult]:
+    """Inverse of ``save_calibration`` (plain arrays only, nothing is unpickled)."""
+    out = {}
+    with np.load(path, allow_pickle=False) as z:
+        for i, key in enumerate(z["keys"]):
+            shape = tuple(int(x) for x in z[f"mask_shape_{i}"])
+            n = int(np.prod(shape))
+            mask = np.unpackbits(z[f"mask_bits_{i}"])[:n].reshape(shape).astype(np.uint8)
+            scores = z[f"scores_{i}"]
+            out[tuple(int(x) for x in key)] = CalibrationResult(
+                mask=mask, repetitive_heads=[int(h) for h in z[f"heads_{i}"]],
+                scores=None if scores.size == 0 else scores, n_prompts=int(z[f"prompts_{i}"][0]))
+    return out
+
+
 @dataclass
 class _Entry:
     pattern: Optional[_b.DevicePattern]
