@@ -15,9 +15,11 @@ and invariants.  No function is "parity unpinned".
 from .attention import (  # noqa: F401
     bf16_bits_to_f64,
     expand_block_mask,
+    f16_bits_to_f64,
     restricted_softmax_rows,
     sparse_attention,
     sparse_attention_blocks,
+    sparse_attention_lse,
 )
 from .anchor import anchor_attention, anchor_rows, anchor_token_maps, nearest_anchor, spatial_similarity, spatial_similarity_rows  # noqa: F401
 from .calibration import block_energy, block_energy_rows, epsilon_schedule, schedule_base_level, select_blocks, select_row, vote  # noqa: F401

@@ -33,6 +33,26 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
     return u32.view(np.float32).astype(np.float64)
 
 
+def f16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of IEEE binary16 bit patterns (uint16) to fp64, field by field."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.int64)
+    sign = np.where(b >> 15, -1.0, 1.0)
+    exp = (b >> 10) & 0x1F
+    frac = (b & 0x3FF).astype(np.float64)
+    normal = (1.0 + frac / 1024.0) * np.exp2((exp - 15).astype(np.float64))
+    subnormal = (frac / 1024.0) * 2.0 ** -14
+    special = np.where(frac == 0, np.inf, np.nan)
+    return sign * np.where(exp == 0, subnormal, np.where(exp == 31, special, normal))
+
+
+def _to_f64(bits: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "bf16":
+        return bf16_bits_to_f64(bits)
+    if dtype == "f16":
+        return f16_bits_to_f64(bits)
+    raise ValueError(dtype)
+
+
 def expand_block_mask(mask_row: np.ndarray, block_k: int, n_keys: int) -> np.ndarray:
     """Per-key boolean for one query block: key j is visible iff its block
     j // block_k is kept (Section 3.2: entry 1 = computed, 0 = skipped)."""
@@ -69,6 +89,7 @@ def sparse_attention(
     block_q: int,
     block_k: int,
     return_probs: bool = False,
+    dtype: str = "bf16",
 ):
     """Full output, fp64 [B, H, N, D].
 
@@ -89,9 +110,9 @@ def sparse_attention(
     probs = np.zeros((B, H, N, N), dtype=np.float64) if return_probs else None
     for b in range(B):
         for h in range(H):
-            qf = bf16_bits_to_f64(q_bits[b, h])
-            kf = bf16_bits_to_f64(k_bits[b, h])
-            vf = bf16_bits_to_f64(v_bits[b, h])
+            qf = _to_f64(q_bits[b, h], dtype)
+            kf = _to_f64(k_bits[b, h], dtype)
+            vf = _to_f64(v_bits[b, h], dtype)
             for r in range(nbq):
                 if rep[h, r] >= 0:
                     continue
@@ -120,6 +141,7 @@ def sparse_attention_blocks(
     block_q: int,
     block_k: int,
     items: Iterable[Tuple[int, int, int]],
+    dtype: str = "bf16",
 ) -> List[np.ndarray]:
     """Outputs of selected query blocks only: for each (b, h, r) in ``items`` an
     fp64 array [rows_in_block_r, D].  Same arithmetic as ``sparse_attention``;
@@ -135,9 +157,9 @@ def sparse_attention_blocks(
         if key not in cache:
             cache.clear()
             cache[key] = (
-                bf16_bits_to_f64(q_bits[b, h]),
-                bf16_bits_to_f64(k_bits[b, h]),
-                bf16_bits_to_f64(v_bits[b, h]),
+                _to_f64(q_bits[b, h], dtype),
+                _to_f64(k_bits[b, h], dtype),
+                _to_f64(v_bits[b, h], dtype),
             )
         qf, kf, vf = cache[key]
         n_rows = min((r + 1) * block_q, N) - r * block_q
@@ -146,3 +168,35 @@ def sparse_attention_blocks(
         o, _ = _block_output(qf, kf, vf, mask[h, rr], rr, scale, block_q, block_k, N)
         results.append(o[:n_rows].copy())
     return results
+
+
+def sparse_attention_lse(q_bits, k_bits, mask, repeat, scale: float, block_q: int, block_k: int, dtype: str = "bf16") -> np.ndarray:
+    """Per query the natural logarithm of the normaliser of Eq. 1 restricted to
+    the kept keys: log sum_{j kept} exp(scale * q_i . k_j), fp64 [B, H, N]; -inf
+    for a query that keeps no key; the rows of a repeated block carry the values
+    of the leading rows of their source block."""
+    B, H, N, D = q_bits.shape
+    nbq = -(-N // block_q)
+    rep = np.full((H, nbq), -1, dtype=np.int64) if repeat is None else np.asarray(repeat, dtype=np.int64)
+    mask = np.asarray(mask)
+    out = np.full((B, H, N), -np.inf, dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            qf, kf = _to_f64(q_bits[b, h], dtype), _to_f64(k_bits[b, h], dtype)
+            for r in range(nbq):
+                if rep[h, r] >= 0:
+                    continue
+                rows = slice(r * block_q, min((r + 1) * block_q, N))
+                visible = expand_block_mask(mask[h, r], block_k, N)
+                if not visible.any():
+                    continue
+                s = scale * (qf[rows] @ kf[visible].T)
+                m = s.max(axis=1)
+                out[b, h, rows] = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+            for r in range(nbq):
+                src = int(rep[h, r])
+                if src < 0:
+                    continue
+                n_rows = min((r + 1) * block_q, N) - r * block_q
+                out[b, h, r * block_q : r * block_q + n_rows] = out[b, h, src * block_q : src * block_q + n_rows]
+    return out

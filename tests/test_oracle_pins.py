@@ -360,3 +360,78 @@ def test_pins_catch_mutant(mutant):
         except AssertionError:
             failed.append(pin.__name__)
     assert failed, f"no pin catches {mutant.__name__}"
+
+
+# ---------------------------------------------------------------------------
+# fp16 inputs and the log-sum-exp output
+# ---------------------------------------------------------------------------
+def test_f16_widening_matches_numpy_for_every_bit_pattern():
+    from oracle import f16_bits_to_f64
+
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = f16_bits_to_f64(bits)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    ok = ~np.isnan(want)
+    assert np.array_equal(got[ok], want[ok]) and np.array_equal(np.signbit(got[ok]), np.signbit(want[ok]))
+
+
+def test_f16_inputs_equal_the_same_values_given_as_bf16():
+    """Values representable in both formats must give identical results whichever way they come in."""
+    rng = np.random.default_rng(21)
+    vals = (rng.integers(-8, 9, (1, 2, 24, 8)) / 4.0).astype(np.float32)  # multiples of 1/4: exact in bf16 and fp16
+    as_bf16 = f32_to_bf16_bits(vals)
+    as_f16 = vals.astype(np.float16).view(np.uint16)
+    mask, repeat = random_mask(22, 2, 3, 3, 0.6, 0.3, keep_diagonal=True)
+    a = sparse_attention(as_bf16, as_bf16, as_bf16, mask, repeat, 0.3, 8, 8)
+    b = sparse_attention(as_f16, as_f16, as_f16, mask, repeat, 0.3, 8, 8, dtype="f16")
+    assert np.array_equal(a, b)
+
+
+def test_lse_brute_force_and_library():
+    from oracle import sparse_attention_lse
+
+    rng = np.random.default_rng(23)
+    B, H, N, D, bq, bk = 1, 2, 13, 4, 4, 3
+    q, k = _bits(rng, (B, H, N, D), 1.5), _bits(rng, (B, H, N, D), 1.5)
+    nbq, nbk = -(-N // bq), -(-N // bk)
+    mask, repeat = random_mask(24, H, nbq, nbk, 0.5, 0.3, keep_diagonal=True, tail_partial=True)
+    mask[0, 1, :] = 0  # a row without kept keys
+    got = sparse_attention_lse(q, k, mask, repeat, 0.4, bq, bk)
+    qf, kf = bf16_bits_to_f64(q), bf16_bits_to_f64(k)
+    for h in range(H):
+        for i in range(N):
+            r = i // bq
+            src = int(repeat[h, r])
+            i_src = i if src < 0 else src * bq + (i - r * bq)
+            r_src = i_src // bq
+            terms = [math.exp(0.4 * float(qf[0, h, i_src] @ kf[0, h, j])) for j in range(N) if mask[h, r_src, j // bk]]
+            want = math.log(sum(terms)) if terms else -math.inf
+            assert (got[0, h, i] == want) if not terms else abs(got[0, h, i] - want) < 1e-12, (h, i)
+    # all-ones mask: torch.logsumexp
+    dense = sparse_attention_lse(q, k, np.ones((H, 1, 1), np.uint8), None, 0.4, N, N)
+    ref = torch.logsumexp(0.4 * torch.from_numpy(qf) @ torch.from_numpy(kf).transpose(-1, -2), dim=-1).numpy()
+    np.testing.assert_allclose(dense, ref, rtol=1e-13)
+
+
+def test_lse_merges_results_over_disjoint_key_sets():
+    """Outputs over two disjoint masks, weighted by exp(lse), give the output over their union."""
+    from oracle import sparse_attention_lse
+
+    rng = np.random.default_rng(25)
+    B, H, N, D, blk = 1, 1, 24, 4, 4
+    q, k, v = (_bits(rng, (B, H, N, D), 1.5) for _ in range(3))
+    nb = N // blk
+    m1 = (rng.random((H, nb, nb)) < 0.5).astype(np.uint8)
+    m2 = ((rng.random((H, nb, nb)) < 0.5) & (m1 == 0)).astype(np.uint8)
+    m1[:, :, 0] = 1
+    m2[:, :, 0] = 0
+    m2[:, :, 1] = 1
+    m1[:, :, 1] = 0
+    o1, o2 = (sparse_attention(q, k, v, m, None, 0.5, blk, blk) for m in (m1, m2))
+    l1, l2 = (sparse_attention_lse(q, k, m, None, 0.5, blk, blk) for m in (m1, m2))
+    w1, w2 = np.exp(l1)[..., None], np.exp(l2)[..., None]
+    merged = (w1 * o1 + w2 * o2) / (w1 + w2)
+    union = sparse_attention(q, k, v, m1 | m2, None, 0.5, blk, blk)
+    np.testing.assert_allclose(merged, union, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(np.log(np.exp(l1) + np.exp(l2)), sparse_attention_lse(q, k, m1 | m2, None, 0.5, blk, blk), rtol=1e-13)
