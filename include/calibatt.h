@@ -212,6 +212,33 @@ int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, const void *v
                                      const calibatt_strides *out_strides, void *stream);
 
 /*
+ * The forward with every option.  `options` (HOST, required):
+ *   in_strides, out_strides  NULL = packed [B][H][N][D], else as in the _strided call
+ *   dtype   CALIBATT_BF16 (the models of the paper) or CALIBATT_F16: element
+ *           type of q, k, v, out; accumulation is fp32 either way and the
+ *           probabilities are rounded to that type for the second contraction
+ *   lse     NULL, or DEVICE fp32 packed [B][H][N] (tensor heads): receives for
+ *           every query the natural logarithm of the sum over its kept keys
+ *           of exp(scale * q.k), -inf for a query that keeps no key; queries of
+ *           a repeated block receive the value of their source row.  With it,
+ *           results over disjoint key sets can be merged exactly.
+ * Everything else as in calibatt_sparse_attn_fwd.
+ * Errors: as calibatt_sparse_attn_fwd_strided; NULL (options), UNSUPPORTED
+ * (dtype), SHAPE (lse not 4-byte aligned).
+ */
+enum { CALIBATT_BF16 = 0, CALIBATT_F16 = 1 };
+typedef struct calibatt_fwd_options {
+  const calibatt_strides *in_strides;
+  const calibatt_strides *out_strides;
+  int32_t dtype;
+  float *lse;
+} calibatt_fwd_options;
+int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const void *v, void *out, int B, int H,
+                                int N, int D, int block_q, int block_k,
+                                const calibatt_pattern *pattern, float scale,
+                                const calibatt_fwd_options *options, void *stream);
+
+/*
  * Spatial-row anchor scheme (Section 3.3; "Inference stage" of Section 3.4:
  * heads flagged as spatially repetitive run dense attention on a reduced query
  * set and broadcast the result).

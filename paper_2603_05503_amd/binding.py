@@ -23,6 +23,11 @@ class _CStrides(C.Structure):
     _fields_ = [("b", C.c_int64), ("h", C.c_int64), ("n", C.c_int64)]
 
 
+class _CFwdOptions(C.Structure):
+    _fields_ = [("in_strides", C.POINTER(_CStrides)), ("out_strides", C.POINTER(_CStrides)),
+                ("dtype", C.c_int32), ("lse", C.c_void_p)]
+
+
 class _CPattern(C.Structure):
     _fields_ = [
         ("H", C.c_int32), ("N", C.c_int32), ("block_q", C.c_int32), ("block_k", C.c_int32),
@@ -119,6 +124,12 @@ def load_library():
     lib.calibatt_spatial_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p,
                                                 C.c_void_p]
+    lib.calibatt_sparse_attn_fwd_ex.restype = C.c_int
+    lib.calibatt_sparse_attn_fwd_ex.argtypes = [
+        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+        C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+        C.POINTER(_CPattern), C.c_float, C.POINTER(_CFwdOptions), C.c_void_p,
+    ]
     lib.calibatt_anchor_attn_fwd_strided.restype = C.c_int
     lib.calibatt_anchor_attn_fwd_strided.argtypes = lib.calibatt_anchor_attn_fwd.argtypes[:-1] + [
         C.POINTER(_CStrides), C.POINTER(_CStrides), C.c_void_p]
@@ -295,35 +306,43 @@ class DevicePattern:
 
 
 def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
-                    block_q: Optional[int] = None, block_k: Optional[int] = None, stream=None):
-    """calibatt_sparse_attn_fwd on torch bf16 CUDA tensors of logical shape [B, H, N, D].  The tensors
-    may be strided views (e.g. ``x.transpose(1, 2)`` of a [B, N, H, D] tensor, or slices of a fused
-    [B, N, 3, H, D] projection) as long as D is contiguous and q, k, v share their strides; then the
-    strided entry point is used."""
+                    block_q: Optional[int] = None, block_k: Optional[int] = None, stream=None, lse=None):
+    """The sparse forward on torch CUDA tensors of logical shape [B, H, N, D], bf16 or fp16 (all four
+    alike).  The tensors may be strided views (e.g. ``x.transpose(1, 2)`` of a [B, N, H, D] tensor, or
+    slices of a fused [B, N, 3, H, D] projection) as long as D is contiguous and q, k, v share their
+    strides.  ``lse``: optional contiguous fp32 CUDA tensor [B, H, N] that receives the log-sum-exp of
+    every query's kept logits.  Packed bf16 calls without ``lse`` go through calibatt_sparse_attn_fwd,
+    everything else through calibatt_sparse_attn_fwd_ex."""
     import torch
 
     lib = load_library()
     for t in (q, k, v, out):
-        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.dim() == 4 and t.stride(3) == 1):
-            raise ValueError("q, k, v, out must be bf16 CUDA tensors [B, H, N, D] with contiguous D")
-        if t.shape != q.shape:
-            raise ValueError("q, k, v, out must have the same shape")
+        if not (t.is_cuda and t.dtype in (torch.bfloat16, torch.float16) and t.dim() == 4 and t.stride(3) == 1):
+            raise ValueError("q, k, v, out must be bf16 or fp16 CUDA tensors [B, H, N, D] with contiguous D")
+        if t.shape != q.shape or t.dtype != q.dtype:
+            raise ValueError("q, k, v, out must have the same shape and element type")
     if not (q.stride() == k.stride() == v.stride()):
         raise ValueError("q, k, v must share their strides")
     B, H, N, D = q.shape
+    if lse is not None and not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous()
+                                and tuple(lse.shape) == (B, H, N)):
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [B, H, N]")
     bq = pattern.host.block_q if block_q is None else block_q
     bk = pattern.host.block_k if block_k is None else block_k
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
-    if all(t.is_contiguous() for t in (q, k, v, out)):
+    packed = all(t.is_contiguous() for t in (q, k, v, out))
+    if packed and lse is None and q.dtype == torch.bfloat16:
         st = lib.calibatt_sparse_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
                                           B, H, N, D, bq, bk, C.byref(pattern.c), float(scale), C.c_void_p(stream))
     else:
         si = _CStrides(q.stride(0), q.stride(1), q.stride(2))
         so = _CStrides(out.stride(0), out.stride(1), out.stride(2))
-        st = lib.calibatt_sparse_attn_fwd_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                                                  B, H, N, D, bq, bk, C.byref(pattern.c), float(scale),
-                                                  C.byref(si), C.byref(so), C.c_void_p(stream))
+        opt = _CFwdOptions(None if packed else C.pointer(si), None if packed else C.pointer(so),
+                           0 if q.dtype == torch.bfloat16 else 1, None if lse is None else lse.data_ptr())
+        st = lib.calibatt_sparse_attn_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                             B, H, N, D, bq, bk, C.byref(pattern.c), float(scale),
+                                             C.byref(opt), C.c_void_p(stream))
     if st != 0:
         raise CalibattError(st, "calibatt_sparse_attn_fwd")
     return out

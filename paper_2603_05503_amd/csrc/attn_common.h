@@ -134,6 +134,42 @@ struct ResidencyClock {
   }
 };
 
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+
+// Element type of q, k, v, out (and of the probabilities fed to the second
+// contraction).  Operands travel as raw 16-byte words; the traits supply the
+// MFMA, the round-to-nearest-even packing of two fp32 values, and the sum of a
+// packed pair accumulated into fp32 (a dot product with a vector of ones).
+struct Bf16 {
+  static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t pack(float lo, float hi) {
+    bf16x2 t;
+    t[0] = (__bf16)lo;
+    t[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, t);
+  }
+  static __device__ __forceinline__ float add_pair(uint32_t pk, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+  }
+};
+struct F16 {
+  static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t pack(float lo, float hi) {
+    f16x2 t;
+    t[0] = (_Float16)lo;
+    t[1] = (_Float16)hi;
+    return __builtin_bit_cast(uint32_t, t);
+  }
+  static __device__ __forceinline__ float add_pair(uint32_t pk, float acc) {
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pk), __builtin_bit_cast(f16x2, 0x3c003c00u), acc, false);
+  }
+};
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   bf16x2 t;
   t[0] = (__bf16)lo;

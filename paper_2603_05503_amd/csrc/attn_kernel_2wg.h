@@ -38,8 +38,9 @@ namespace calibatt_dev {
 // BK-key tiles.  Holds the per-lane state (Q^T operand, O^T accumulators,
 // running max / sum) and the LDS addressing; the kernels decide which rows,
 // which tiles, and where the result goes.
-template <int D, int BQ, int BK>
+template <int D, int BQ, int BK, typename T = Bf16>
 struct RowBlock {
+  using Operand = u32x4;  // eight 16-bit elements of an MFMA operand, as raw bits
   static constexpr int NW = BQ / 32;     // wavefronts per workgroup
   static constexpr int NT = NW * 64;     // threads
   static constexpr int CH = D / 8;       // 16-byte chunks per row
@@ -59,7 +60,7 @@ struct RowBlock {
   uint32_t k_lane_off, v_lane_off, ldsK_wave, ldsV_wave;
   uint32_t kv_row_bytes;  // distance between consecutive K (and V) rows in memory
   uint32_t k_addr0, v_addr[DB];
-  bf16x8 qreg[DS];  // Q^T as MFMA B operand: lane (query l32, half g) holds d = 16 s + 8 g + [0,8)
+  Operand qreg[DS];  // Q^T as MFMA B operand: lane (query l32, half g) holds d = 16 s + 8 g + [0,8)
   f32x16 o[DB];
   float m_run;  // running max of scaled (log2-domain) logits, shared by lane and lane^32
   float l_run;  // this lane's share of the running row sum
@@ -107,10 +108,10 @@ struct RowBlock {
   }
 
   // A query row as MFMA B operand: `qrow_ptr` points at the D bf16 of this lane's row.
-  __device__ __forceinline__ void load_q(const uint16_t *qrow_ptr, bf16x8 (&dst)[DS]) const {
+  __device__ __forceinline__ void load_q(const uint16_t *qrow_ptr, Operand (&dst)[DS]) const {
     const uint16_t *qp = qrow_ptr + 8 * g;
 #pragma unroll
-    for (int s = 0; s < DS; ++s) dst[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+    for (int s = 0; s < DS; ++s) dst[s] = *reinterpret_cast<const Operand *>(qp + 16 * s);
     // touch the registers here so that the compiler's wait for these loads sits
     // in front of the tile loop and not inside it
 #pragma unroll
@@ -132,7 +133,7 @@ struct RowBlock {
   // s_acc[kb][v] = dot(key 32 kb + 16 (v >> 3) + 8 g + (v & 7), query l32), unscaled.
   __device__ __forceinline__ void scores(uint32_t buf_off, f32x16 (&s_acc)[KB]) const { scores(buf_off, s_acc, qreg); }
   // The same against an explicit query operand (see load_q).
-  __device__ __forceinline__ void scores(uint32_t buf_off, f32x16 (&s_acc)[KB], const bf16x8 (&q)[DS]) const {
+  __device__ __forceinline__ void scores(uint32_t buf_off, f32x16 (&s_acc)[KB], const Operand (&q)[DS]) const {
     const char *const kbuf = ldsK + buf_off;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
@@ -140,21 +141,21 @@ struct RowBlock {
       for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.f;
     // k-slab outer, key sub-block inner: consecutive MFMAs hit different
     // accumulators; the A operands of slab s+1 are read while slab s multiplies.
-    bf16x8 ka[2][KB];
+    Operand ka[2][KB];
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
-      ka[0][kb] = *reinterpret_cast<const bf16x8 *>(kbuf + (k_addr0 + kb * 32 * ROWB));
+      ka[0][kb] = *reinterpret_cast<const Operand *>(kbuf + (k_addr0 + kb * 32 * ROWB));
 #pragma unroll
     for (int s = 0; s < DS; ++s) {
       if (s + 1 < DS) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
           ka[(s + 1) & 1][kb] =
-              *reinterpret_cast<const bf16x8 *>(kbuf + ((k_addr0 ^ ((s + 1) << 5)) + kb * 32 * ROWB));
+              *reinterpret_cast<const Operand *>(kbuf + ((k_addr0 ^ ((s + 1) << 5)) + kb * 32 * ROWB));
       }
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
-        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][kb], q[s], s_acc[kb], 0, 0, 0);
+        s_acc[kb] = T::mfma(ka[s & 1][kb], q[s], s_acc[kb]);
     }
     __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);  // LDS reads of slab 0
 #pragma unroll
@@ -220,16 +221,15 @@ struct RowBlock {
     // denominator of the final division see the same probabilities.
     float psum = 0.f;
     uint32_t pb[KB][8];  // bf16 pairs: pb[kb][4*s2 + j] = keys (2j, 2j+1) of 16-key slab s2
-    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v], sc_t, -m_new));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][v + 1], sc_t, -m_new));
-        const uint32_t pk = pack_bf16(p0, p1);
+        const uint32_t pk = T::pack(p0, p1);
         pb[kb][v >> 1] = pk;
-        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, psum, false);
+        psum = T::add_pair(pk, psum);
       }
     l_run = l_run * alpha + psum;
     if (__any(alpha != 1.0f)) {
@@ -262,10 +262,10 @@ struct RowBlock {
         if (j + 1 < 2 * KB) v_read(j + 1, (j + 1) & 1);
         const int kb = j >> 1, s2 = j & 1;
         const u32x4 pw = {pb[kb][4 * s2 + 0], pb[kb][4 * s2 + 1], pb[kb][4 * s2 + 2], pb[kb][4 * s2 + 3]};
-        const bf16x8 pB = __builtin_bit_cast(bf16x8, pw);
+
 #pragma unroll
         for (int db = 0; db < DB; ++db)
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[j & 1][db]), pB, o[db], 0, 0, 0);
+          o[db] = T::mfma(va[j & 1][db], pw, o[db]);
       }
       __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
 #pragma unroll
@@ -279,10 +279,11 @@ struct RowBlock {
     if (has_next) issue_v(Vres, c_next);
   }
 
-  // Normalise and stage the BQ x D bf16 result in LDS: row i at lds + i * OST.
+  // Normalise and stage the BQ x D result in LDS: row i at lds + i * OST.
   // A row that saw no key is all zero.  Ends with a barrier: the tile is
-  // complete for every thread on return.
-  __device__ __forceinline__ void stage_result() {
+  // complete for every thread on return.  Returns the natural logarithm of the
+  // sum of exp(scaled logit) over the keys this lane's row saw (-inf for none).
+  __device__ __forceinline__ float stage_result() {
     const float l_tot = sum_with_other_half(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     __syncthreads();
@@ -292,11 +293,13 @@ struct RowBlock {
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         u32x2 w;
-        w[0] = pack_bf16(o[db][4 * a + 0] * inv, o[db][4 * a + 1] * inv);
-        w[1] = pack_bf16(o[db][4 * a + 2] * inv, o[db][4 * a + 3] * inv);
+        w[0] = T::pack(o[db][4 * a + 0] * inv, o[db][4 * a + 1] * inv);
+        w[1] = T::pack(o[db][4 * a + 2] * inv, o[db][4 * a + 3] * inv);
         *reinterpret_cast<u32x2 *>(orow + (32 * db + 8 * a + 4 * g) * 2) = w;
       }
     __syncthreads();
+    // m_run is the maximum of the logits times log2(e), l_tot the sum of 2^(logit - m_run)
+    return l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
   }
 };
 
@@ -309,14 +312,16 @@ constexpr int IV_COLS = 2048;
 // row as runs of consecutive key blocks, one word per run (low half = first
 // block, high half = kept blocks of the row before the run) plus a terminating
 // word per row, and the workgroup expands them into LDS.
-template <int D, int BQ, int BK, bool IV = false>
+// T: element type of q, k, v, out (Bf16 or F16).  lse: NULL, or fp32 [B][H][N] (tensor heads)
+// receiving per query the natural log of the sum of exp(scaled logit) over its kept keys.
+template <int D, int BQ, int BK, bool IV = false, typename T = Bf16>
 __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_kernel(
     const uint16_t *__restrict__ gq, const uint16_t *__restrict__ gk, const uint16_t *__restrict__ gv,
     uint16_t *__restrict__ gout, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const int32_t *__restrict__ work, const int32_t *__restrict__ fan_ptr, const int32_t *__restrict__ fan_dst,
     int32_t *counter, const FwdDims p, const int32_t *__restrict__ iv_ptr, const uint32_t *__restrict__ iv,
-    const int32_t *__restrict__ head_map) {
-  using RB = RowBlock<D, BQ, BK>;
+    const int32_t *__restrict__ head_map, float *__restrict__ lse) {
+  using RB = RowBlock<D, BQ, BK, T>;
   constexpr int NT = RB::NT, CH = RB::CH, ROWB = RB::ROWB, OST = RB::OST, LDS_BYTES = RB::LDS_BYTES;
 
   // LDS_BYTES + 64 (work-item mailbox) [+ IV_COLS * 4 (column list) if IV]
@@ -432,9 +437,16 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void sparse_attn_fwd_k
   }
 
   // ---- normalise, stage in LDS, store to the block and its repeat targets ----
-  rb.stage_result();
+  const float row_lse = rb.stage_result();
   const int fbeg = fan_ptr[item];
   const int fend = fan_ptr[item + 1];
+  if (lse && head_ok && rb.g == 0) {  // one lane per query row; repeated blocks copy the value as well
+    float *const lse_head = lse + ((size_t)b * p.H + ht) * (size_t)N;
+    for (int f = fbeg - 1; f < fend; ++f) {
+      const int row = (f < fbeg ? r : fan_dst[f]) * BQ + rb.row_in_block();
+      if (row < N) lse_head[row] = row_lse;
+    }
+  }
   uint16_t *const out_head = gout + (size_t)b * p.out.b + (size_t)ht * p.out.h;
   for (int f = fbeg - 1; head_ok && f < fend; ++f) {
     const int rd = f < fbeg ? r : fan_dst[f];

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(SIM_BQ * 2, 2) void pair_similarity_kernel(
   const int tok = valid ? tok_raw : p.n_tok - 1;
   int par = partner[tok];
   par = par < 0 ? 0 : (par < N ? par : N - 1);
-  bf16x8 q_t[DS], q_a[DS];
+  typename RB::Operand q_t[DS], q_a[DS];
   rb.load_q(gq + head_off + (size_t)tok * D, q_t);
   rb.load_q(gq + head_off + (size_t)par * D, q_a);
 

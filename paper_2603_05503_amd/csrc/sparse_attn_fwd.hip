@@ -25,6 +25,8 @@ struct FwdPtrs {
   const int32_t *iv_ptr;  // interval form of the kept-block lists, or NULL
   const uint32_t *iv;
   const int32_t *head_map;  // tensor head of each pattern head, or NULL
+  float *lse;               // log-sum-exp output, or NULL
+  int dtype;                // CALIBATT_BF16 or CALIBATT_F16
 };
 
 // Per-device launch facts, looked up once per kernel and device.
@@ -70,7 +72,7 @@ int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, c
   if (counter && items > slots) grid = slots; else counter = nullptr;
   if constexpr (TAKES_IV)
     return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
-                         a.work, a.fan_ptr, a.fan_dst, counter, p, a.iv_ptr, a.iv, a.head_map);
+                         a.work, a.fan_ptr, a.fan_dst, counter, p, a.iv_ptr, a.iv, a.head_map, a.lse);
   else
     return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
                          a.work, a.fan_ptr, a.fan_dst, counter, p);
@@ -93,6 +95,19 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
   if (items <= 0) return CALIBATT_OK;
   if (items > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
   int slots = 0;
+  if (a.dtype == CALIBATT_F16) {  // fp16 tensors: the two-workgroup kernel only
+    static DevInfo info[2][64];
+    if (a.iv) {
+      constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + IV_COLS * 4;
+      auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, true, F16>;
+      if (int st = prepare(kernel, BQ * 2, SMEM, info[1], slots)) return st;
+      return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
+    }
+    constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64;
+    auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, false, F16>;
+    if (int st = prepare(kernel, BQ * 2, SMEM, info[0], slots)) return st;
+    return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
+  }
   if (a.iv) {  // interval-encoded pattern: read by the two-workgroup kernel only
     static DevInfo info[64];
     constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + IV_COLS * 4;
@@ -103,7 +118,7 @@ int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) 
   // the alternative kernels read packed [B][H][N][D] tensors only
   const bool packed = p.in.n == D && p.in.h == (long long)p.N * D && p.in.b == (long long)p.H * p.N * D &&
                       p.out.n == D && p.out.h == (long long)p.N * D && p.out.b == (long long)p.H * p.N * D;
-  const Variant variant = packed && !a.head_map ? wanted_variant() : Variant::TwoWg;
+  const Variant variant = packed && !a.head_map && !a.lse ? wanted_variant() : Variant::TwoWg;
   if constexpr (BQ <= BK) {
     if (variant == Variant::PingPong) {
       static DevInfo info[64];
@@ -311,6 +326,25 @@ extern "C" int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, co
                                                 const calibatt_strides *in_strides,
                                                 const calibatt_strides *out_strides, void *stream) {
   if (!in_strides || !out_strides) return CALIBATT_ERR_NULL;
+  calibatt_fwd_options opt;
+  opt.in_strides = in_strides;
+  opt.out_strides = out_strides;
+  opt.dtype = CALIBATT_BF16;
+  opt.lse = nullptr;
+  return calibatt_sparse_attn_fwd_ex(q, k, v, out, B, H, N, D, block_q, block_k, pattern, scale, &opt, stream);
+}
+
+extern "C" int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const void *v, void *out, int B, int H,
+                                           int N, int D, int block_q, int block_k,
+                                           const calibatt_pattern *pattern, float scale,
+                                           const calibatt_fwd_options *options, void *stream) {
+  if (!options) return CALIBATT_ERR_NULL;
+  if (options->dtype != CALIBATT_BF16 && options->dtype != CALIBATT_F16) return CALIBATT_ERR_UNSUPPORTED;
+  if (B <= 0 || H <= 0 || N <= 0 || D <= 0) return q && k && v && out && pattern ? CALIBATT_ERR_SHAPE : CALIBATT_ERR_NULL;
+  const calibatt_strides packed_strides = {(int64_t)H * N * D, (int64_t)N * D, (int64_t)D};
+  const calibatt_strides *in_strides = options->in_strides ? options->in_strides : &packed_strides;
+  const calibatt_strides *out_strides = options->out_strides ? options->out_strides : &packed_strides;
+  if (options->lse && ((uintptr_t)options->lse & 3)) return CALIBATT_ERR_SHAPE;
   if (!q || !k || !v || !out || !pattern) return CALIBATT_ERR_NULL;
   if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || block_q <= 0 || block_k <= 0) return CALIBATT_ERR_SHAPE;
   if (!(D == 64 || D == 128) || !(block_q == 64 || block_q == 128) || !(block_k == 64 || block_k == 128))
@@ -349,6 +383,8 @@ extern "C" int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, co
   a.iv_ptr = intervals ? pattern->iv_ptr : nullptr;
   a.iv = intervals ? pattern->iv : nullptr;
   a.head_map = pattern->head_map;
+  a.lse = options->lse;
+  a.dtype = options->dtype;
   FwdDims p;
   p.B = B;
   p.H = H;
