@@ -39,7 +39,7 @@ def parse_args():
     ap.add_argument("--workload", default="wan480", choices=["tiny", "wan480", "wan720", "mochi"])
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--repeat-frac", type=float, default=None)
-    ap.add_argument("--order", type=int, default=3)
+    ap.add_argument("--order", type=int, default=4)
     ap.add_argument("--heads", type=int, default=None)
     ap.add_argument("--no-dense", action="store_true", help="skip the all-ones reference run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")

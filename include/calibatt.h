@@ -68,6 +68,12 @@ enum {
                                   by count descending, then dealing order of the head, then r; then the
                                   other blocks head by head in dealing order, r ascending.  Segments
                                   follow each other in group order. */
+  ,
+  CALIBATT_ORDER_XCD_HEADS_TAIL = 4 /* as CALIBATT_ORDER_XCD_HEADS, except that the other blocks of the
+                                  LAST head of every group (in dealing order) come by count
+                                  descending, then r: a group's queue then ends with its shortest
+                                  blocks, which shortens the idle tail of the persistent workgroups
+                                  while all earlier heads keep their blocks together. */
 };
 #define CALIBATT_GROUPS 8
 
@@ -96,7 +102,7 @@ typedef struct calibatt_pattern {
   const int32_t *fan_ptr;    /* [n_work + 1] offsets into fan_dst, per work item */
   const int32_t *fan_dst;    /* [n_repeat] query blocks that copy work item i, ascending */
   int32_t *work_counter;     /* NULL, or DEVICE int32[16] workspace, see calibatt_sparse_attn_fwd */
-  int32_t n_groups;          /* 1, or CALIBATT_GROUPS for CALIBATT_ORDER_XCD_HEADS */
+  int32_t n_groups;          /* 1, or CALIBATT_GROUPS for the two CALIBATT_ORDER_XCD_HEADS* orders */
   int32_t group_ptr[CALIBATT_GROUPS + 1]; /* segment g of `work` is [group_ptr[g], group_ptr[g+1]) */
   /* Optional interval form of the kept-block lists (calibatt_encode_intervals): when both are
    * non-NULL the forward reads them and never touches col_idx, which may then be NULL. */

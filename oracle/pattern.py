@@ -31,8 +31,11 @@ work[n_work]        ids h*nbq + r of the non-repeated blocks in schedule order:
                              then r; after them the remaining blocks head by
                              head in dealing order, r ascending.  Group 0's
                              segment comes first, then group 1, ...
-group_ptr[9]        order 3: start of each group's segment in work, last entry
-                    n_work.  Other orders: one group, [0, n_work, n_work, ...].
+                    order 4: as order 3, except that the remaining blocks of
+                             the LAST head of every group (in dealing order) are
+                             listed by count descending, then r.
+group_ptr[9]        orders 3, 4: start of each group's segment in work, last
+                    entry n_work.  Other orders: one group, [0, n_work, ...].
 fan_ptr[n_work+1], fan_dst[n_repeat]
                     for work item i the ascending list of blocks r' of the same
                     head with repeat[h, r'] == r.
@@ -98,7 +101,7 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
     """Returns a dict of int32 arrays: row_ptr, col_idx, repeat_src, work,
     fan_ptr, fan_dst, plus ints nbq, nbk, nnz, n_work, n_repeat."""
     nbq, nbk = _dims(H, N, block_q, block_k)
-    if order not in (0, 1, 2, 3):
+    if order not in (0, 1, 2, 3, 4):
         raise PatternError("unsupported", f"order={order}")
     mask = np.asarray(mask).reshape(H, nbq, nbk)
     rep = np.full((H, nbq), -1, dtype=np.int64) if repeat is None else np.asarray(repeat, dtype=np.int64).reshape(H, nbq)
@@ -120,7 +123,7 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
     elif order == 2:
         items.sort(key=lambda hr: (hr[0], -counts[hr], hr[1]))
     group_ptr = [0] + [len(items)] * N_GROUPS
-    if order == 3:
+    if order in (3, 4):
         weight = [sum(counts[(h, r)] for r in range(nbq)) for h in range(H)]
         load = [0] * N_GROUPS
         members = [[] for _ in range(N_GROUPS)]
@@ -136,7 +139,12 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
             live = [(h, r) for h in members[g] for r in range(nbq) if rep[h, r] < 0]
             rank = {h: i for i, h in enumerate(members[g])}
             items.extend(sorted((hr for hr in live if is_long(hr)), key=lambda hr: (-counts[hr], rank[hr[0]], hr[1])))
-            items.extend(hr for hr in live if not is_long(hr))
+            rest = [hr for hr in live if not is_long(hr)]
+            if order == 4 and members[g]:
+                last = members[g][-1]
+                head_rows = sorted((hr for hr in rest if hr[0] == last), key=lambda hr: (-counts[hr], hr[1]))
+                rest = [hr for hr in rest if hr[0] != last] + head_rows
+            items.extend(rest)
             group_ptr.append(len(items))
     work = [h * nbq + r for (h, r) in items]
 
@@ -151,5 +159,5 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
         nbq=nbq, nbk=nbk, nnz=len(col_idx), n_work=len(work), n_repeat=len(fan_dst),
         row_ptr=i32(row_ptr), col_idx=i32(col_idx), repeat_src=i32(rep),
         work=i32(work), fan_ptr=i32(fan_ptr), fan_dst=i32(fan_dst),
-        n_groups=N_GROUPS if order == 3 else 1, group_ptr=i32(group_ptr),
+        n_groups=N_GROUPS if order in (3, 4) else 1, group_ptr=i32(group_ptr),
     )

@@ -88,8 +88,9 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
                                         calibatt_pattern *out) {
   if (!mask || !row_ptr || !col_idx || !repeat_src || !work || !fan_ptr || !fan_dst || !out)
     return CALIBATT_ERR_NULL;
-  if (order < CALIBATT_ORDER_NATURAL || order > CALIBATT_ORDER_XCD_HEADS)
+  if (order < CALIBATT_ORDER_NATURAL || order > CALIBATT_ORDER_XCD_HEADS_TAIL)
     return CALIBATT_ERR_UNSUPPORTED;
+  const bool xcd_groups = order == CALIBATT_ORDER_XCD_HEADS || order == CALIBATT_ORDER_XCD_HEADS_TAIL;
   Dims d;
   int st = make_dims(H, N, block_q, block_k, d);
   if (st) return st;
@@ -131,7 +132,7 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
       int32_t w = 0;
       for (int64_t i = 0; i < d.rows; ++i)
         if (repeat_src[i] < 0) work[w++] = (int32_t)i;
-    } else if (order == CALIBATT_ORDER_XCD_HEADS) {
+    } else if (xcd_groups) {
       // Deal heads, heaviest first, to the currently lightest group.
       std::vector<int64_t> weight((size_t)H);
       for (int h = 0; h < H; ++h)
@@ -166,9 +167,17 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
           return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
         });
         for (int32_t i : longs) work[w++] = i;
-        for (int h : members[g])
+        for (int h : members[g]) {
+          const int32_t head_begin = w;
           for (int64_t i = (int64_t)h * d.nbq; i < (int64_t)(h + 1) * d.nbq; ++i)
             if (repeat_src[i] < 0 && !is_long(i)) work[w++] = (int32_t)i;
+          // the group's last head ends the queue: longest first, so that the last items handed
+          // out are the shortest ones (stable: r ascending among equal counts)
+          if (order == CALIBATT_ORDER_XCD_HEADS_TAIL && h == members[g].back())
+            std::stable_sort(work + head_begin, work + w, [&](int32_t a, int32_t b) {
+              return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
+            });
+        }
       }
       group_ptr[CALIBATT_GROUPS] = w;
     } else {
@@ -229,7 +238,7 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
   out->iv_ptr = nullptr;
   out->iv = nullptr;
   out->head_map = nullptr;
-  out->n_groups = order == CALIBATT_ORDER_XCD_HEADS ? CALIBATT_GROUPS : 1;
+  out->n_groups = xcd_groups ? CALIBATT_GROUPS : 1;
   for (int g = 0; g <= CALIBATT_GROUPS; ++g) out->group_ptr[g] = group_ptr[g];
   return CALIBATT_OK;
 }

@@ -115,7 +115,7 @@ class _Entry:
 class CalibAttention:
     def __init__(self, H: int, N: int, D: int, block_q: int = 128, block_k: int = 128,
                  geometry: Optional[Tuple[int, int, int]] = None, anchors: int = 5,
-                 intervals: bool = True, order: int = 3, device: str = "cuda"):
+                 intervals: bool = True, order: int = 4, device: str = "cuda"):
         self.H, self.N, self.D = H, N, D
         self.block_q, self.block_k = block_q, block_k
         self.intervals, self.order, self.device = intervals, order, device

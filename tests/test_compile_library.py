@@ -67,7 +67,7 @@ def test_library_matches_oracle_random(seed):
     mask = mask * rng.integers(1, 255, size=mask.shape).astype(np.uint8)
     if seed % 5 == 0:
         repeat = None
-    for order in (0, 1, 2, 3):
+    for order in (0, 1, 2, 3, 4):
         a = _lib_compile(mask, repeat, H, N, bq, bk, order)
         b = oracle_compile(mask, repeat, H, N, bq, bk, order)
         _assert_equal(a, b)
@@ -79,7 +79,7 @@ def test_library_matches_oracle_random(seed):
 @pytest.mark.parametrize("name", ["tiny", "wan480", "mochi"])
 def test_library_matches_oracle_named_configs(name):
     wl = make_workload(name, with_qkv=False, heads=None if name == "tiny" else 11)
-    for order in (0, 1, 2, 3):
+    for order in (0, 1, 2, 3, 4):
         a = _lib_compile(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, order)
         b = oracle_compile(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, order)
         _assert_equal(a, b)

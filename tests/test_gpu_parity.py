@@ -56,7 +56,7 @@ def test_random_masks(lib, D, bq, bk, B, H, N, dens, rep, gain):
     nbq, nbk = -(-N // bq), -(-N // bk)
     mask, repeat = random_mask(seed + 1, H, nbq, nbk, dens, rep, tail_partial=(N % bq) != 0)
     scale = 1.0 / math.sqrt(D)
-    for order in (0, 1, 2, 3):
+    for order in (0, 1, 2, 3, 4):
         got, _ = run_gpu(lib, q, k, v, mask, repeat, scale, bq, bk, order=order)
         want = sparse_attention(q, k, v, mask, repeat, scale, bq, bk)
         st = assert_parity(got, want, f"order {order}")

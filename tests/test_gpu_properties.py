@@ -97,7 +97,7 @@ def test_run_to_run_bitwise_and_scheduler_independent(lib, persistent):
     mask, repeat = random_mask(12, H, nb, nb, 0.3, 0.2, keep_diagonal=True, tail_partial=True)
     tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
     ref = None
-    for order in (0, 1, 2, 3, 1):
+    for order in (0, 1, 2, 3, 4, 1):
         dp = lib.compile_pattern(mask, repeat, H, N, blk, blk, order).to_device(persistent=persistent)
         for _ in range(2):  # the second call also checks that the work counter was re-armed
             out = torch.zeros_like(tq)

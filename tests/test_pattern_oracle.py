@@ -67,7 +67,10 @@ def independent_numpy_compile(mask, repeat, H, N, bq, bk, order):
         c_live = counts[ids]
         long_ = 2 * c_live * ids.size > 3 * c_live.sum()
         # one lexsort: group, long rows before the others, then (count desc for long rows), head rank, r
-        perm = np.lexsort((rr, rank_in_group[hh], np.where(long_, -c_live, 0), ~long_, group_of[hh]))
+        # (order 4: the rows of a group's last head that are not long come by count descending)
+        last_head = rank_in_group[hh] == np.array(size)[group_of[hh]] - 1
+        tail_key = np.where((order == 4) & last_head & ~long_, -c_live, 0)
+        perm = np.lexsort((rr, tail_key, rank_in_group[hh], np.where(long_, -c_live, 0), ~long_, group_of[hh]))
         group_ptr = np.concatenate([[0], np.cumsum(np.bincount(group_of[hh], minlength=8))])
     work = ids[perm]
     fan = [np.flatnonzero(rep[w // nbq] == w % nbq) for w in work]
@@ -111,7 +114,7 @@ def check_invariants(p, mask, repeat, H, N, bq, bk, order):
         assert (np.diff(cnt) <= 0).all()
     if order == 2:
         assert (np.diff(work // nbq) >= 0).all()
-    if order == 3:
+    if order in (3, 4):
         gp = p["group_ptr"]
         assert p["n_groups"] == 8 and gp[0] == 0 and gp[8] == p["n_work"] and (np.diff(gp) >= 0).all()
         heads_of = [sorted(set((work[gp[g] : gp[g + 1]] // nbq).tolist())) for g in range(8)]
@@ -124,9 +127,16 @@ def check_invariants(p, mask, repeat, H, N, bq, bk, order):
             is_long = 2 * c_seg * p["n_work"] > 3 * p["nnz"]
             n_long = int(is_long.sum())
             assert is_long[:n_long].all() and (np.diff(c_seg[:n_long]) <= 0).all()
-            for h in set(hs[n_long:].tolist()):
+            rest_heads = hs[n_long:].tolist()
+            for h in set(rest_heads):
                 idx = np.flatnonzero(hs[n_long:] == h)
-                assert (np.diff(idx) == 1).all() and (np.diff(seg[n_long:][idx]) > 0).all()
+                assert (np.diff(idx) == 1).all()
+                if order == 4 and h == rest_heads[-1]:
+                    # the head that ends the queue: count descending, r ascending among equal counts
+                    c_h, r_h = c_seg[n_long:][idx], seg[n_long:][idx]
+                    assert (np.diff(c_h) <= 0).all() and (np.diff(r_h)[np.diff(c_h) == 0] > 0).all()
+                else:
+                    assert (np.diff(seg[n_long:][idx]) > 0).all()
         # greedy dealing keeps the groups within one head's weight of each other
         w = np.array([cnt[gp[g] : gp[g + 1]].sum() for g in range(8)])
         per_head = {}
@@ -152,7 +162,7 @@ def test_oracle_vs_independent_construction(seed):
     dens = float(rng.choice([0.0, 0.1, 0.5, 0.9, 1.0]))
     mask, repeat = random_mask(seed, H, nbq, nbk, dens, float(rng.choice([0, 0.2, 0.6])), tail_partial=(N % bq) != 0)
     mask = mask * rng.integers(1, 255, size=mask.shape).astype(np.uint8)  # any non-zero byte = kept
-    for order in (0, 1, 2, 3):
+    for order in (0, 1, 2, 3, 4):
         p = compile_pattern(mask, repeat, H, N, bq, bk, order)
         q = independent_numpy_compile(mask, repeat, H, N, bq, bk, order)
         for name in q:
