@@ -69,11 +69,12 @@ enum {
                                   other blocks head by head in dealing order, r ascending.  Segments
                                   follow each other in group order. */
   ,
-  CALIBATT_ORDER_XCD_HEADS_TAIL = 4 /* as CALIBATT_ORDER_XCD_HEADS, except that the other blocks of the
-                                  LAST head of every group (in dealing order) come by count
-                                  descending, then r: a group's queue then ends with its shortest
-                                  blocks, which shortens the idle tail of the persistent workgroups
-                                  while all earlier heads keep their blocks together. */
+  CALIBATT_ORDER_XCD_HEADS_TAIL = 4 /* heads dealt to groups as for CALIBATT_ORDER_XCD_HEADS; a group's
+                                  segment lists its heads in dealing order and, within a head, the
+                                  blocks by count descending, then r.  Every head, and with it the
+                                  group's queue, ends with its shortest blocks: heads change over
+                                  sharply (few heads live at a time) and the persistent workgroups'
+                                  idle tail is short. */
 };
 #define CALIBATT_GROUPS 8
 

@@ -31,9 +31,9 @@ work[n_work]        ids h*nbq + r of the non-repeated blocks in schedule order:
                              then r; after them the remaining blocks head by
                              head in dealing order, r ascending.  Group 0's
                              segment comes first, then group 1, ...
-                    order 4: as order 3, except that the remaining blocks of
-                             the LAST head of every group (in dealing order) are
-                             listed by count descending, then r.
+                    order 4: groups as for order 3; a group's segment lists
+                             its heads in dealing order and, within a head, the
+                             blocks by count descending, then r.
 group_ptr[9]        orders 3, 4: start of each group's segment in work, last
                     entry n_work.  Other orders: one group, [0, n_work, ...].
 fan_ptr[n_work+1], fan_dst[n_repeat]
@@ -138,13 +138,12 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
         for g in range(N_GROUPS):
             live = [(h, r) for h in members[g] for r in range(nbq) if rep[h, r] < 0]
             rank = {h: i for i, h in enumerate(members[g])}
-            items.extend(sorted((hr for hr in live if is_long(hr)), key=lambda hr: (-counts[hr], rank[hr[0]], hr[1])))
-            rest = [hr for hr in live if not is_long(hr)]
-            if order == 4 and members[g]:
-                last = members[g][-1]
-                head_rows = sorted((hr for hr in rest if hr[0] == last), key=lambda hr: (-counts[hr], hr[1]))
-                rest = [hr for hr in rest if hr[0] != last] + head_rows
-            items.extend(rest)
+            if order == 3:
+                items.extend(sorted((hr for hr in live if is_long(hr)), key=lambda hr: (-counts[hr], rank[hr[0]], hr[1])))
+                items.extend(hr for hr in live if not is_long(hr))
+            else:
+                for h in members[g]:
+                    items.extend(sorted((hr for hr in live if hr[0] == h), key=lambda hr: (-counts[hr], hr[1])))
             group_ptr.append(len(items))
     work = [h * nbq + r for (h, r) in items]
 

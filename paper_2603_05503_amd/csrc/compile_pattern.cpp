@@ -166,17 +166,22 @@ extern "C" int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repe
         std::stable_sort(longs.begin(), longs.end(), [&](int32_t a, int32_t b) {
           return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
         });
-        for (int32_t i : longs) work[w++] = i;
-        for (int h : members[g]) {
-          const int32_t head_begin = w;
-          for (int64_t i = (int64_t)h * d.nbq; i < (int64_t)(h + 1) * d.nbq; ++i)
-            if (repeat_src[i] < 0 && !is_long(i)) work[w++] = (int32_t)i;
-          // the group's last head ends the queue: longest first, so that the last items handed
-          // out are the shortest ones (stable: r ascending among equal counts)
-          if (order == CALIBATT_ORDER_XCD_HEADS_TAIL && h == members[g].back())
+        if (order == CALIBATT_ORDER_XCD_HEADS) {
+          for (int32_t i : longs) work[w++] = i;
+          for (int h : members[g])
+            for (int64_t i = (int64_t)h * d.nbq; i < (int64_t)(h + 1) * d.nbq; ++i)
+              if (repeat_src[i] < 0 && !is_long(i)) work[w++] = (int32_t)i;
+        } else {
+          // head by head, each head's blocks longest first (stable: r ascending among equal counts):
+          // every head, and with it the group's queue, ends with its shortest blocks
+          for (int h : members[g]) {
+            const int32_t head_begin = w;
+            for (int64_t i = (int64_t)h * d.nbq; i < (int64_t)(h + 1) * d.nbq; ++i)
+              if (repeat_src[i] < 0) work[w++] = (int32_t)i;
             std::stable_sort(work + head_begin, work + w, [&](int32_t a, int32_t b) {
               return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
             });
+          }
         }
       }
       group_ptr[CALIBATT_GROUPS] = w;

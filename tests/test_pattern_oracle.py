@@ -66,11 +66,12 @@ def independent_numpy_compile(mask, repeat, H, N, bq, bk, order):
             heapq.heappush(heap, (load + int(weight[h]), g))
         c_live = counts[ids]
         long_ = 2 * c_live * ids.size > 3 * c_live.sum()
-        # one lexsort: group, long rows before the others, then (count desc for long rows), head rank, r
-        # (order 4: the rows of a group's last head that are not long come by count descending)
-        last_head = rank_in_group[hh] == np.array(size)[group_of[hh]] - 1
-        tail_key = np.where((order == 4) & last_head & ~long_, -c_live, 0)
-        perm = np.lexsort((rr, tail_key, rank_in_group[hh], np.where(long_, -c_live, 0), ~long_, group_of[hh]))
+        if order == 3:
+            # one lexsort: group, long rows before the others, then (count desc for long rows), head rank, r
+            perm = np.lexsort((rr, rank_in_group[hh], np.where(long_, -c_live, 0), ~long_, group_of[hh]))
+        else:
+            # order 4: group, head rank, count descending, r
+            perm = np.lexsort((rr, -c_live, rank_in_group[hh], group_of[hh]))
         group_ptr = np.concatenate([[0], np.cumsum(np.bincount(group_of[hh], minlength=8))])
     work = ids[perm]
     fan = [np.flatnonzero(rep[w // nbq] == w % nbq) for w in work]
@@ -122,21 +123,22 @@ def check_invariants(p, mask, repeat, H, N, bq, bk, order):
         for g in range(8):
             seg = work[gp[g] : gp[g + 1]]
             hs = seg // nbq
-            # long rows lead, longest first; after them a head's rows are contiguous and ascending
             c_seg = cnt[gp[g] : gp[g + 1]]
-            is_long = 2 * c_seg * p["n_work"] > 3 * p["nnz"]
-            n_long = int(is_long.sum())
-            assert is_long[:n_long].all() and (np.diff(c_seg[:n_long]) <= 0).all()
-            rest_heads = hs[n_long:].tolist()
-            for h in set(rest_heads):
-                idx = np.flatnonzero(hs[n_long:] == h)
-                assert (np.diff(idx) == 1).all()
-                if order == 4 and h == rest_heads[-1]:
-                    # the head that ends the queue: count descending, r ascending among equal counts
-                    c_h, r_h = c_seg[n_long:][idx], seg[n_long:][idx]
+            if order == 3:
+                # long rows lead, longest first; after them a head's rows are contiguous and ascending
+                is_long = 2 * c_seg * p["n_work"] > 3 * p["nnz"]
+                n_long = int(is_long.sum())
+                assert is_long[:n_long].all() and (np.diff(c_seg[:n_long]) <= 0).all()
+                for h in set(hs[n_long:].tolist()):
+                    idx = np.flatnonzero(hs[n_long:] == h)
+                    assert (np.diff(idx) == 1).all() and (np.diff(seg[n_long:][idx]) > 0).all()
+            else:
+                # a head's rows are contiguous, longest first, r ascending among equal counts
+                for h in set(hs.tolist()):
+                    idx = np.flatnonzero(hs == h)
+                    assert (np.diff(idx) == 1).all()
+                    c_h, r_h = c_seg[idx], seg[idx]
                     assert (np.diff(c_h) <= 0).all() and (np.diff(r_h)[np.diff(c_h) == 0] > 0).all()
-                else:
-                    assert (np.diff(seg[n_long:][idx]) > 0).all()
         # greedy dealing keeps the groups within one head's weight of each other
         w = np.array([cnt[gp[g] : gp[g + 1]].sum() for g in range(8)])
         per_head = {}
