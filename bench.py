@@ -226,7 +226,7 @@ def profiled_traffic(args):
     """HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this
     exact command line (default workload and schedule); None for anything else."""
     if args.workload != "wan480" or args.density is not None or args.repeat_frac is not None \
-            or args.heads is not None or args.order != 3 or args.no_persistent:
+            or args.heads is not None or args.order != 4 or args.no_persistent or args.intervals:
         return None
     path = os.path.join(ROOT, "profiles", "sparse_attn_fwd_wan480.txt")
     try:
