@@ -315,6 +315,48 @@ int calibatt_anchor_attn_fwd_strided(const void *q, const void *k, const void *v
                                      const calibatt_strides *out_strides, void *stream);
 
 /*
+ * The anchor forward with the tail of its work evened out (Section 3.3 / 3.4,
+ * anchor benchmark of the supplement: few anchors mean few computed queries).
+ * Every unit of work (128 computed queries of one head against all keys) takes
+ * the same time, so the units run in rounds of as many as the GPU holds at a
+ * time and the last round may be mostly empty.  This call cuts the units of
+ * that last round into n_split parts of the keys each, runs the parts side by
+ * side, and merges them: with lse_s the log-sum-exp of the scaled logits of
+ * part s and A_s its softmax-weighted values, the result is
+ * sum_s e^(lse_s - m) A_s / sum_s e^(lse_s - m), m = max_s lse_s, which is the
+ * softmax over all keys of Eq. 1-2.  Same outputs as
+ * calibatt_anchor_attn_fwd_strided up to fp32 rounding of the merge (compare
+ * with the tolerance of the forward, not bitwise); receivers of one computed
+ * query still hold the same bits.
+ *
+ * calibatt_anchor_split_plan (needs a current HIP device; no GPU work): for the
+ * shape (B, N, D, n_heads, n_q) writes n_split in [1, 8] (1 = splitting gains
+ * nothing: the forward then ignores the workspace) and the bytes of workspace
+ * the forward needs on this device (0 for n_split 1).  Errors: NULL, SHAPE,
+ * UNSUPPORTED, LAUNCH.
+ *
+ * calibatt_anchor_attn_fwd_split: arguments as calibatt_anchor_attn_fwd_strided,
+ * plus
+ * workspace        DEVICE, 16-byte aligned, workspace_bytes long, owned by the
+ *                  caller, contents irrelevant before and undefined after; it
+ *                  is written and read by the call's kernels only, so one
+ *                  buffer may serve successive calls on one stream, never
+ *                  calls that may overlap.  NULL: every unit is computed whole
+ *                  (the plain call).
+ * workspace_bytes  at least what calibatt_anchor_split_plan returns for the
+ *                  shape, else BUFFER_TOO_SMALL.
+ */
+int calibatt_anchor_split_plan(int B, int N, int D, int n_heads, int n_q, int32_t *n_split,
+                               int64_t *workspace_bytes);
+int calibatt_anchor_attn_fwd_split(const void *q, const void *k, const void *v, void *out, int B, int H,
+                                   int N, int D, const int32_t *head_ids, int n_heads,
+                                   const int32_t *q_index, const int32_t *dst_ptr,
+                                   const int32_t *dst_idx, int n_q, float scale,
+                                   const calibatt_strides *in_strides,
+                                   const calibatt_strides *out_strides, void *workspace,
+                                   int64_t workspace_bytes, void *stream);
+
+/*
  * Detection of spatially repetitive heads (Section 3.3): the spatial
  * similarity score of a head is the cosine similarity between the attention
  * rows of a spatial row of tokens and those of its nearest anchor row (same

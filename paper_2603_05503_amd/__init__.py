@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     HostAnchorMap,
     HostPattern,
     anchor_attn_fwd,
+    anchor_split_plan,
     anchor_map,
     anchor_partner,
     block_energy,

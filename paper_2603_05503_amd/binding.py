@@ -133,6 +133,11 @@ def load_library():
     lib.calibatt_anchor_attn_fwd_strided.restype = C.c_int
     lib.calibatt_anchor_attn_fwd_strided.argtypes = lib.calibatt_anchor_attn_fwd.argtypes[:-1] + [
         C.POINTER(_CStrides), C.POINTER(_CStrides), C.c_void_p]
+    lib.calibatt_anchor_attn_fwd_split.restype = C.c_int
+    lib.calibatt_anchor_attn_fwd_split.argtypes = lib.calibatt_anchor_attn_fwd_strided.argtypes[:-1] + [
+        C.c_void_p, C.c_int64, C.c_void_p]
+    lib.calibatt_anchor_split_plan.restype = C.c_int
+    lib.calibatt_anchor_split_plan.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_int32), C.POINTER(C.c_int64)]
     lib.calibatt_strerror.restype = C.c_char_p
     lib.calibatt_strerror.argtypes = [C.c_int]
     lib.calibatt_version.restype = C.c_int
@@ -390,10 +395,21 @@ class DeviceAnchorMap:
         self.dst_idx = torch.from_numpy(np.ascontiguousarray(hm.dst_idx, dtype=np.int32)).to(device)
 
 
-def anchor_attn_fwd(q, k, v, out, head_ids, amap: DeviceAnchorMap, scale: float, stream=None):
+def anchor_split_plan(B: int, N: int, D: int, n_heads: int, n_q: int):
+    """calibatt_anchor_split_plan on the current device: (n_split, workspace_bytes)."""
+    lib = load_library()
+    n_split, nbytes = C.c_int32(0), C.c_int64(0)
+    st = lib.calibatt_anchor_split_plan(B, N, D, n_heads, n_q, C.byref(n_split), C.byref(nbytes))
+    if st != 0:
+        raise CalibattError(st, "calibatt_anchor_split_plan")
+    return n_split.value, nbytes.value
+
+
+def anchor_attn_fwd(q, k, v, out, head_ids, amap: DeviceAnchorMap, scale: float, stream=None, workspace=None):
     """calibatt_anchor_attn_fwd on torch bf16 CUDA tensors of logical shape [B, H, N, D] (strided views
     with contiguous D allowed, q, k, v sharing their strides); ``head_ids`` is an int32 CUDA tensor of
-    the heads to process."""
+    the heads to process.  ``workspace``: a contiguous CUDA tensor of at least the bytes
+    ``anchor_split_plan`` names for the shape selects calibatt_anchor_attn_fwd_split."""
     import torch
 
     lib = load_library()
@@ -412,7 +428,14 @@ def anchor_attn_fwd(q, k, v, out, head_ids, amap: DeviceAnchorMap, scale: float,
     args = (q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, D,
             head_ids.data_ptr(), head_ids.numel(), amap.q_index.data_ptr(),
             amap.dst_ptr.data_ptr(), amap.dst_idx.data_ptr(), amap.n_q, float(scale))
-    if all(t.is_contiguous() for t in (q, k, v, out)):
+    if workspace is not None:
+        if not (workspace.is_cuda and workspace.is_contiguous() and workspace.device == q.device):
+            raise ValueError("workspace must be a contiguous CUDA tensor on the tensors' device")
+        si = _CStrides(q.stride(0), q.stride(1), q.stride(2))
+        so = _CStrides(out.stride(0), out.stride(1), out.stride(2))
+        st = lib.calibatt_anchor_attn_fwd_split(*args, C.byref(si), C.byref(so), C.c_void_p(workspace.data_ptr()),
+                                                workspace.numel() * workspace.element_size(), C.c_void_p(stream))
+    elif all(t.is_contiguous() for t in (q, k, v, out)):
         st = lib.calibatt_anchor_attn_fwd(*args, C.c_void_p(stream))
     else:
         si = _CStrides(q.stride(0), q.stride(1), q.stride(2))

@@ -301,6 +301,27 @@ struct RowBlock {
     // m_run is the maximum of the logits times log2(e), l_tot the sum of 2^(logit - m_run)
     return l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
   }
+
+  // Result over a PART of the keys, for a later merge with the other parts: the
+  // rows normalised by their own sum as fp32 (rows[row_in_block][D]) and the
+  // natural logarithm of that sum (row_lse[row_in_block], -inf and a zero row
+  // when no key was seen), straight from the accumulators to global memory.
+  __device__ __forceinline__ void store_partial(float *rows, float *row_lse) const {
+    const float l_tot = sum_with_other_half(l_run);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    float *orow = rows + (size_t)(wave * 32 + l32) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        f32x4 w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = o[db][4 * a + j] * inv;
+        *reinterpret_cast<f32x4 *>(orow + 32 * db + 8 * a + 4 * g) = w;
+      }
+    if (g == 0)
+      row_lse[wave * 32 + l32] = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+  }
 };
 
 // Kept-block columns of a row held in LDS when the pattern comes as intervals

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 
@@ -153,20 +154,82 @@ bool strides_ok(const calibatt_strides &t, int B, int H, int N, int D) {
   return true;
 }
 
+// Key-range split of the anchor path: S in [1, ANCHOR_MAX_SPLIT] minimising the length of the last
+// round of work units on an XCD, ceil(rem * S / slots) / S, with a small charge per part for the
+// merge; 1 when every XCD's range is a whole number of rounds or nothing is gained.
+void plan_anchor_split(AnchorDims &p, int slots_per_xcd) {
+  p.slots = slots_per_xcd;
+  p.n_split = 1;
+  p.rem_max = 0;
+  if (slots_per_xcd <= 0) return;
+  int rem_max = 0;
+  for (int x = 0; x < ANCHOR_XCDS; ++x) {
+    const AnchorRange range(p, x, ANCHOR_XCDS);
+    rem_max = std::max(rem_max, range.n % slots_per_xcd);
+  }
+  if (rem_max == 0) return;
+  int best = 1;
+  double best_cost = 1.0;
+  for (int s = 2; s <= ANCHOR_MAX_SPLIT && s <= p.nbk; ++s) {
+    const double cost = (double)((rem_max * s + slots_per_xcd - 1) / slots_per_xcd) / s + 0.01 * s;
+    if (cost < best_cost - 1e-9) {
+      best_cost = cost;
+      best = s;
+    }
+  }
+  if (best_cost > 0.9) return;  // less than a tenth of a round to gain
+  p.n_split = best;
+  p.rem_max = rem_max;
+}
+
+template <int D>
+long long anchor_workspace_bytes(const AnchorDims &p) {
+  return p.n_split > 1 ? (long long)ANCHOR_XCDS * p.rem_max * p.n_split * AnchorLds<D>::PART_FLOATS * 4 : 0;
+}
+
+// slots of one XCD for the anchor kernel on the current device
+template <int D>
+int anchor_slots(int &slots_per_xcd) {
+  static DevInfo info[64];
+  int slots = 0;
+  if (int st = prepare(anchor_attn_fwd_kernel<D>, ANCHOR_BQ * 2, AnchorLds<D>::BYTES, info, slots)) return st;
+  slots_per_xcd = slots / ANCHOR_XCDS;
+  return CALIBATT_OK;
+}
+
+// workspace == nullptr: every unit whole.  Otherwise the split is planned for the current device and
+// the workspace must hold anchor_workspace_bytes().
 template <int D>
 int launch_anchor(const FwdPtrs &a, const int32_t *head_ids, const int32_t *q_index, const int32_t *dst_ptr,
-                  const int32_t *dst_idx, const AnchorDims &p, hipStream_t stream) {
+                  const int32_t *dst_idx, AnchorDims p, float *workspace, long long workspace_bytes,
+                  hipStream_t stream) {
   const long long units = (long long)p.B * p.n_heads * p.nbq;
   if (units <= 0) return CALIBATT_OK;
-  const long long grid = ANCHOR_XCDS * ((units + ANCHOR_XCDS - 1) / ANCHOR_XCDS);
+  int slots_per_xcd = 0;
+  if (int st = anchor_slots<D>(slots_per_xcd)) return st;
+  p.slots = slots_per_xcd;
+  p.n_split = 1;
+  p.rem_max = 0;
+  if (workspace) {
+    plan_anchor_split(p, slots_per_xcd);
+    if (anchor_workspace_bytes<D>(p) > workspace_bytes) return CALIBATT_ERR_BUFFER_TOO_SMALL;
+  }
+  long long per_xcd = 0;
+  for (int x = 0; x < ANCHOR_XCDS; ++x) {
+    const AnchorRange range(p, x, ANCHOR_XCDS);
+    per_xcd = std::max(per_xcd, (long long)range.whole + (long long)(range.n - range.whole) * p.n_split);
+  }
+  const long long grid = ANCHOR_XCDS * per_xcd;
   if (grid > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
-  static DevInfo info[64];
-  constexpr int SMEM = AnchorLds<D>::BYTES;
-  auto kernel = anchor_attn_fwd_kernel<D>;
-  int slots = 0;
-  if (int st = prepare(kernel, ANCHOR_BQ * 2, SMEM, info, slots)) return st;
-  return launch_kernel(kernel, (unsigned)grid, ANCHOR_BQ * 2, SMEM, stream, a.q, a.k, a.v, a.out, head_ids, q_index,
-                       dst_ptr, dst_idx, p);
+  if (int st = launch_kernel(anchor_attn_fwd_kernel<D>, (unsigned)grid, ANCHOR_BQ * 2, AnchorLds<D>::BYTES, stream, a.q,
+                             a.k, a.v, a.out, head_ids, q_index, dst_ptr, dst_idx, workspace, p))
+    return st;
+  if (p.n_split == 1) return CALIBATT_OK;
+  static DevInfo merge_info[64];
+  int unused = 0;
+  if (int st = prepare(anchor_merge_kernel<D>, ANCHOR_BQ * 2, AnchorLds<D>::MERGE_BYTES, merge_info, unused)) return st;
+  return launch_kernel(anchor_merge_kernel<D>, (unsigned)(ANCHOR_XCDS * p.rem_max), ANCHOR_BQ * 2,
+                       AnchorLds<D>::MERGE_BYTES, stream, a.out, head_ids, dst_ptr, dst_idx, (const float *)workspace, p);
 }
 
 // Dynamic LDS of the energy kernel grows with the number of key blocks; one generous ceiling is
@@ -275,26 +338,11 @@ extern "C" int calibatt_anchor_attn_fwd(const void *q, const void *k, const void
                                           scale, &packed, &packed, stream);
 }
 
-extern "C" int calibatt_anchor_attn_fwd_strided(const void *q, const void *k, const void *v, void *out, int B,
-                                                int H, int N, int D, const int32_t *head_ids, int n_heads,
-                                                const int32_t *q_index, const int32_t *dst_ptr,
-                                                const int32_t *dst_idx, int n_q, float scale,
-                                                const calibatt_strides *in_strides,
-                                                const calibatt_strides *out_strides, void *stream) {
-  if (!q || !k || !v || !out || !in_strides || !out_strides) return CALIBATT_ERR_NULL;
+namespace {
+int fill_anchor_dims(AnchorDims &p, int B, int H, int N, int D, int n_heads, int n_q, float scale,
+                     const calibatt_strides *in_strides, const calibatt_strides *out_strides) {
   if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || n_heads < 0 || n_q < 0) return CALIBATT_ERR_SHAPE;
   if (!(D == 64 || D == 128)) return CALIBATT_ERR_UNSUPPORTED;
-  if (out == q || out == k || out == v) return CALIBATT_ERR_SHAPE;
-  if (!strides_ok(*in_strides, B, H, N, D) || !strides_ok(*out_strides, B, H, N, D)) return CALIBATT_ERR_SHAPE;
-  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return CALIBATT_ERR_SHAPE;
-  if (n_heads == 0 || n_q == 0) return CALIBATT_OK;
-  if (!head_ids || !q_index || !dst_ptr || !dst_idx) return CALIBATT_ERR_NULL;
-  FwdPtrs a{};
-  a.q = (const uint16_t *)q;
-  a.k = (const uint16_t *)k;
-  a.v = (const uint16_t *)v;
-  a.out = (uint16_t *)out;
-  AnchorDims p;
   p.B = B;
   p.H = H;
   p.N = N;
@@ -303,11 +351,66 @@ extern "C" int calibatt_anchor_attn_fwd_strided(const void *q, const void *k, co
   p.nbq = (n_q + ANCHOR_BQ - 1) / ANCHOR_BQ;
   p.nbk = (N + ANCHOR_BK - 1) / ANCHOR_BK;
   p.scale_log2e = scale * 1.4426950408889634f;
-  p.in = Strides{in_strides->b, in_strides->h, in_strides->n};
-  p.out = Strides{out_strides->b, out_strides->h, out_strides->n};
+  if (in_strides) p.in = Strides{in_strides->b, in_strides->h, in_strides->n};
+  if (out_strides) p.out = Strides{out_strides->b, out_strides->h, out_strides->n};
+  p.n_split = 1;
+  p.slots = 0;
+  p.rem_max = 0;
+  return CALIBATT_OK;
+}
+}  // namespace
+
+extern "C" int calibatt_anchor_attn_fwd_strided(const void *q, const void *k, const void *v, void *out, int B,
+                                                int H, int N, int D, const int32_t *head_ids, int n_heads,
+                                                const int32_t *q_index, const int32_t *dst_ptr,
+                                                const int32_t *dst_idx, int n_q, float scale,
+                                                const calibatt_strides *in_strides,
+                                                const calibatt_strides *out_strides, void *stream) {
+  return calibatt_anchor_attn_fwd_split(q, k, v, out, B, H, N, D, head_ids, n_heads, q_index, dst_ptr, dst_idx, n_q,
+                                        scale, in_strides, out_strides, nullptr, 0, stream);
+}
+
+extern "C" int calibatt_anchor_split_plan(int B, int N, int D, int n_heads, int n_q, int32_t *n_split,
+                                          int64_t *workspace_bytes) {
+  if (!n_split || !workspace_bytes) return CALIBATT_ERR_NULL;
+  AnchorDims p{};
+  if (int st = fill_anchor_dims(p, B, 1, N, D, n_heads, n_q, 1.0f, nullptr, nullptr)) return st;
+  *n_split = 1;
+  *workspace_bytes = 0;
+  if (n_heads == 0 || n_q == 0) return CALIBATT_OK;
+  int slots_per_xcd = 0;
+  if (int st = D == 128 ? anchor_slots<128>(slots_per_xcd) : anchor_slots<64>(slots_per_xcd)) return st;
+  plan_anchor_split(p, slots_per_xcd);
+  *n_split = p.n_split;
+  *workspace_bytes = D == 128 ? anchor_workspace_bytes<128>(p) : anchor_workspace_bytes<64>(p);
+  return CALIBATT_OK;
+}
+
+extern "C" int calibatt_anchor_attn_fwd_split(const void *q, const void *k, const void *v, void *out, int B, int H,
+                                              int N, int D, const int32_t *head_ids, int n_heads,
+                                              const int32_t *q_index, const int32_t *dst_ptr,
+                                              const int32_t *dst_idx, int n_q, float scale,
+                                              const calibatt_strides *in_strides,
+                                              const calibatt_strides *out_strides, void *workspace,
+                                              int64_t workspace_bytes, void *stream) {
+  if (!q || !k || !v || !out || !in_strides || !out_strides) return CALIBATT_ERR_NULL;
+  AnchorDims p{};
+  if (int st = fill_anchor_dims(p, B, H, N, D, n_heads, n_q, scale, in_strides, out_strides)) return st;
+  if (out == q || out == k || out == v) return CALIBATT_ERR_SHAPE;
+  if (!strides_ok(*in_strides, B, H, N, D) || !strides_ok(*out_strides, B, H, N, D)) return CALIBATT_ERR_SHAPE;
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)workspace) & 15) return CALIBATT_ERR_SHAPE;
+  if (workspace_bytes < 0) return CALIBATT_ERR_SHAPE;
+  if (n_heads == 0 || n_q == 0) return CALIBATT_OK;
+  if (!head_ids || !q_index || !dst_ptr || !dst_idx) return CALIBATT_ERR_NULL;
+  FwdPtrs a{};
+  a.q = (const uint16_t *)q;
+  a.k = (const uint16_t *)k;
+  a.v = (const uint16_t *)v;
+  a.out = (uint16_t *)out;
   hipStream_t s = (hipStream_t)stream;
-  if (D == 128) return launch_anchor<128>(a, head_ids, q_index, dst_ptr, dst_idx, p, s);
-  return launch_anchor<64>(a, head_ids, q_index, dst_ptr, dst_idx, p, s);
+  if (D == 128)
+    return launch_anchor<128>(a, head_ids, q_index, dst_ptr, dst_idx, p, (float *)workspace, workspace_bytes, s);
+  return launch_anchor<64>(a, head_ids, q_index, dst_ptr, dst_idx, p, (float *)workspace, workspace_bytes, s);
 }
 
 extern "C" int calibatt_sparse_attn_fwd(const void *q, const void *k, const void *v, void *out, int B,

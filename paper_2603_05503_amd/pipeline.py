@@ -121,6 +121,7 @@ class CalibAttention:
         self.intervals, self.order, self.device = intervals, order, device
         self.entries: Dict[Hashable, _Entry] = {}
         self.amap = None
+        self._anchor_workspace: Dict[Tuple[int, int, int], object] = {}
         if geometry is not None:
             F, Hs, Ws = geometry
             self.amap = _b.anchor_map(N, F, Hs, Ws, anchors).to_device(device)
@@ -156,8 +157,23 @@ class CalibAttention:
         if e.pattern is not None:
             _b.sparse_attn_fwd(q, k, v, out, e.pattern, scale, stream=stream)
         if e.head_ids is not None:
-            _b.anchor_attn_fwd(q, k, v, out, e.head_ids, self.amap, scale, stream=stream)
+            _b.anchor_attn_fwd(q, k, v, out, e.head_ids, self.amap, scale, stream=stream,
+                               workspace=self._workspace_for(q, e.head_ids.numel(), stream))
         return out
+
+    def _workspace_for(self, q, n_heads: int, stream):
+        """Workspace of the key-range split of the anchor path, one per (batch, flagged heads, stream):
+        calls on one stream run in order and may share it, calls on different streams may overlap."""
+        import torch
+
+        handle = torch.cuda.current_stream(q.device).cuda_stream if stream is None else int(stream)
+        key = (q.shape[0], n_heads, handle)
+        if key not in self._anchor_workspace:
+            with torch.cuda.device(q.device):
+                n_split, nbytes = _b.anchor_split_plan(q.shape[0], self.N, self.D, n_heads, self.amap.n_q)
+            self._anchor_workspace[key] = (torch.empty(nbytes // 4, dtype=torch.float32, device=q.device)
+                                           if n_split > 1 else None)
+        return self._anchor_workspace[key]
 
     @property
     def index_bytes(self) -> int:

@@ -22,14 +22,25 @@ def _qkv(seed, B, H, N, D, gain=1.0):
     return q, k, v
 
 
-def _run(lib, q, k, v, heads, amap, scale):
+def _run(lib, q, k, v, heads, amap, scale, split=False, expect_split=None):
+    """split: through calibatt_anchor_attn_fwd_split with the workspace its plan asks for
+    (poisoned with NaN: every value the merge reads must have been written by a part)."""
     import torch
 
     tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
     out = torch.empty_like(tq)
     out.view(torch.int16).fill_(POISON)
     hid = torch.tensor(heads, dtype=torch.int32, device="cuda")
-    lib.anchor_attn_fwd(tq, tk, tv, out, hid, amap, scale)
+    workspace = None
+    if split:
+        B, H, N, D = q.shape
+        n_split, nbytes = lib.anchor_split_plan(B, N, D, len(heads), amap.n_q)
+        print(f"  split plan: {n_split} parts, workspace {nbytes} bytes", flush=True)
+        if expect_split is not None:
+            assert (n_split > 1) == expect_split
+        assert (nbytes > 0) == (n_split > 1) and nbytes % 16 == 0
+        workspace = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    lib.anchor_attn_fwd(tq, tk, tv, out, hid, amap, scale, workspace=workspace)
     torch.cuda.synchronize()
     return from_dev(out)
 
@@ -44,14 +55,17 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("split", [False, True], ids=["whole", "split"])
 @pytest.mark.parametrize("B,H,heads,F,Hs,Ws,k,extra,D,gain", CASES)
-def test_anchor_parity(lib, B, H, heads, F, Hs, Ws, k, extra, D, gain):
-    print(f"anchor parity B={B} H={H} heads={heads} F={F} Hs={Hs} Ws={Ws} k={k} extra={extra} D={D}", flush=True)
+def test_anchor_parity(lib, B, H, heads, F, Hs, Ws, k, extra, D, gain, split):
+    print(f"anchor parity B={B} H={H} heads={heads} F={F} Hs={Hs} Ws={Ws} k={k} extra={extra} D={D} split={split}",
+          flush=True)
     N = F * Hs * Ws + extra
     q, kk, v = _qkv(21 + F + Hs + Ws + k, B, H, N, D, gain)
     scale = 1 / math.sqrt(D)
     amap = lib.anchor_map(N, F, Hs, Ws, k).to_device()
-    got = _run(lib, q, kk, v, heads, amap, scale)
+    # these small shapes fill less than one round of the GPU: every unit is split
+    got = _run(lib, q, kk, v, heads, amap, scale, split=split, expect_split=True)
     want = anchor_attention(q, kk, v, heads, F, Hs, Ws, k, scale)
     for i, h in enumerate(heads):
         assert_parity(got[:, h], want[:, i], f"head {h}")
@@ -64,7 +78,8 @@ def test_anchor_parity(lib, B, H, heads, F, Hs, Ws, k, extra, D, gain):
         assert (got[:, h] == got[:, h][:, q_index[src]]).all()
 
 
-def test_custom_lists_and_invalid_entries_are_safe(lib):
+@pytest.mark.parametrize("split", [False, True], ids=["whole", "split"])
+def test_custom_lists_and_invalid_entries_are_safe(lib, split):
     """Lists that do not come from the geometry: rows nobody names stay untouched,
     receivers outside [0, N) are skipped, query indices are clamped, an invalid
     head id is skipped."""
@@ -79,7 +94,7 @@ def test_custom_lists_and_invalid_entries_are_safe(lib):
     dst_ptr = np.concatenate([[0], np.cumsum([len(d) for d in dst])]).astype(np.int32)
     dst_idx = np.array([t for d in dst for t in d], np.int32)
     amap = HostAnchorMap(N=N, n_q=5, q_index=q_index, dst_ptr=dst_ptr, dst_idx=dst_idx).to_device()
-    got = _run(lib, q, k, v, [1, 7, -1], amap, 0.09)
+    got = _run(lib, q, k, v, [1, 7, -1], amap, 0.09, split=split)
     from oracle.anchor import dense_rows
     from oracle import bf16_bits_to_f64
 
@@ -99,7 +114,8 @@ def test_custom_lists_and_invalid_entries_are_safe(lib):
     assert (got[0, 0] == POISON).all()
 
 
-def test_long_receiver_lists(lib):
+@pytest.mark.parametrize("split", [False, True], ids=["whole", "split"])
+def test_long_receiver_lists(lib, split):
     """One computed query broadcast to more receivers than one staging chunk holds."""
     from paper_2603_05503_amd.binding import HostAnchorMap
 
@@ -111,7 +127,7 @@ def test_long_receiver_lists(lib):
     dst_ptr = np.concatenate([[0], np.cumsum([len(d) for d in dst])]).astype(np.int32)
     dst_idx = np.array([t for d in dst for t in d], np.int32)
     amap = HostAnchorMap(N=N, n_q=3, q_index=q_index, dst_ptr=dst_ptr, dst_idx=dst_idx).to_device()
-    got = _run(lib, q, k, v, [0], amap, 0.125)
+    got = _run(lib, q, k, v, [0], amap, 0.125, split=split)
     assert (got[0, 0, :2500] == got[0, 0, 0]).all()
     assert (got[0, 0, 2501:] == got[0, 0, 2501]).all()
     from oracle.anchor import dense_rows
@@ -123,10 +139,12 @@ def test_long_receiver_lists(lib):
         assert np.abs(bits_to_f64(got[0, 0, t]) - rows[i]).max() <= MAX_ABS
 
 
-def test_wan480_k5_sampled_parity(lib):
+@pytest.mark.parametrize("split", [False, True], ids=["whole", "split"])
+def test_wan480_k5_sampled_parity(lib, split):
     """The paper's setting (Wan 480p geometry, k = 5) on a few heads of the full
     shape: sampled computed queries against the oracle, every token bitwise
-    against the anchor it copies, a second run bit for bit."""
+    against the anchor it copies, a second run bit for bit.  With two heads the
+    86 units leave 10-11 per XCD, all in the last round: with `split` each is cut."""
     import torch
     from oracle.anchor import dense_rows
     from oracle import bf16_bits_to_f64
@@ -138,8 +156,8 @@ def test_wan480_k5_sampled_parity(lib):
     scale = 1 / math.sqrt(D)
     amap = lib.anchor_map(N, F, Hs, Ws, k).to_device()
     heads = [3, 1]
-    got = _run(lib, q, kk, v, heads, amap, scale)
-    again = _run(lib, q, kk, v, heads, amap, scale)
+    got = _run(lib, q, kk, v, heads, amap, scale, split=split, expect_split=True)
+    again = _run(lib, q, kk, v, heads, amap, scale, split=split)
     assert (got == again).all()
     q_index, src = anchor_token_maps(N, F, Hs, Ws, k)
     for h in heads:
@@ -155,3 +173,43 @@ def test_wan480_k5_sampled_parity(lib):
         worst, total, n = max(worst, float(d.max())), total + float(d.sum()), n + d.size
     print(f"max_abs {worst:.3e} mean_abs {total / n:.3e}", flush=True)
     assert worst <= MAX_ABS and total / n <= MEAN_ABS
+
+
+def test_split_workspace_too_small_is_refused(lib):
+    """A workspace shorter than the plan asks for is an error, not a fault."""
+    import torch
+    from paper_2603_05503_amd.binding import CalibattError
+
+    print("anchor split: short workspace", flush=True)
+    B, H, F, Hs, Ws, k, D = 1, 2, 3, 7, 20, 3, 128
+    N = F * Hs * Ws
+    q, kk, v = _qkv(80, B, H, N, D)
+    amap = lib.anchor_map(N, F, Hs, Ws, k).to_device()
+    n_split, nbytes = lib.anchor_split_plan(B, N, D, 2, amap.n_q)
+    assert n_split > 1 and nbytes > 16
+    tq, tk, tv = to_dev(q), to_dev(kk), to_dev(v)
+    out = torch.empty_like(tq)
+    hid = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    small = torch.empty(nbytes // 4 - 4, dtype=torch.float32, device="cuda")
+    with pytest.raises(CalibattError) as e:
+        lib.anchor_attn_fwd(tq, tk, tv, out, hid, amap, 0.1, workspace=small)
+    assert e.value.status == -7
+
+
+def test_split_plan_at_the_paper_shapes(lib):
+    """Wan 480p, 40 heads (supplement, anchor benchmark): k = 5 leaves 215 units per
+    XCD, 23 beyond three full rounds of 64, cut in two; k = 30 (every row) leaves
+    none to gain from on a 64-slot XCD only if the plan says so - the plan is
+    checked against its own definition here."""
+    N, D, H = 21 * 30 * 52, 128, 40
+    for k in (1, 2, 3, 4, 5, 10, 15, 30):
+        n_q = 21 * k * 52
+        n_split, nbytes = lib.anchor_split_plan(1, N, D, H, n_q)
+        units = H * -(-n_q // 128)
+        rem = max((units * (x + 1) // 8 - units * x // 8) % 64 for x in range(8))
+        cost = lambda s: -(-rem * s // 64) / s + 0.01 * s
+        best = min(range(1, 9), key=lambda s: (cost(s) if s > 1 else 1.0, s))
+        want = best if rem and cost(best) <= 0.9 and best > 1 else 1
+        print(f"  k={k}: units {units}, rem {rem}, n_split {n_split}, workspace {nbytes / 2**20:.1f} MiB", flush=True)
+        assert n_split == want
+        assert nbytes == (8 * rem * n_split * (128 * D + 128) * 4 if n_split > 1 else 0)
