@@ -144,8 +144,23 @@ def energy_leg(pkg, torch, q, k, wl, steps):
     t = sum(ms) / len(ms)
     flops = 4.0 * wl.N * wl.N * wl.D * wl.H * wl.B
     row_sums = E.sum(dim=-1)
+    # the rest of a calibration step on the device: Eq. 6 at eps = 0.9 and one vote per block
+    masks = pkg.select_blocks_device(E, 0.9)
+    counts = torch.zeros(masks.shape[1:], dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    sel = []
+    for _ in range(steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        pkg.select_blocks_device(E, 0.9, out=masks)
+        for bi in range(masks.shape[0]):
+            pkg.vote_accumulate_device(masks[bi], counts)
+        b.record(stream)
+        torch.cuda.synchronize()
+        sel.append(a.elapsed_time(b))
     return {"ms": t, "tflops": flops / (t * 1e-3) / 1e12,
-            "max_row_sum_error": float((row_sums - 1).abs().max())}
+            "max_row_sum_error": float((row_sums - 1).abs().max()),
+            "select_and_vote_ms": sum(sel) / len(sel), "kept_fraction_at_eps_0.9": float(masks.float().mean())}
 
 
 def similarity_leg(pkg, torch, q, k, wl, steps, anchors=5):

@@ -442,6 +442,30 @@ int calibatt_vote_accumulate(const uint8_t *mask, int64_t n, uint16_t *counts);
 int calibatt_vote_finish(const uint16_t *counts, int n_prompts, int64_t n, double rho, uint8_t *out);
 
 /*
+ * The two per-prompt steps on the GPU, so that a calibration step (block
+ * energy, Eq. 6, one more vote for Eq. 8-9) never leaves it; only the counters
+ * come back, once, for calibatt_vote_finish.
+ *
+ * calibatt_select_blocks_device: Eq. 6 exactly as calibatt_select_blocks defines
+ * it (same order, same fp64 running sum in that order), bit for bit the same
+ * mask; energies must not be NaN (the order is then unspecified; nothing
+ * faults).
+ *   energy  DEVICE, fp32 [n_rows][nbk], 4-byte aligned, e.g. the output of
+ *           calibatt_block_energy        mask  DEVICE, uint8 [n_rows][nbk]
+ * Supported: nbk <= 4096.  Errors: NULL, SHAPE, UNSUPPORTED, LAUNCH.
+ *
+ * calibatt_vote_accumulate_device: counts[i] += (mask[i] != 0) on DEVICE
+ * buffers (counts 2-byte aligned, zeroed by the caller before the first
+ * prompt).  A counter at 65535 stays there (the host routine refuses instead).
+ * Errors: NULL, SHAPE, LAUNCH.
+ *
+ * Both only enqueue work on `stream` (hipStream_t, NULL = default stream).
+ */
+int calibatt_select_blocks_device(const float *energy, int64_t n_rows, int nbk, double eps, uint8_t *mask,
+                                  void *stream);
+int calibatt_vote_accumulate_device(const uint8_t *mask, int64_t n, uint16_t *counts, void *stream);
+
+/*
  * Energy threshold of diffusion step t of T (Eq. 7): A + (C - A) exp(-k t / T),
  * t = 0 the highest-noise step.  Returns NaN when T <= 0.
  * calibatt_schedule_base_level: the base level A the paper uses in the

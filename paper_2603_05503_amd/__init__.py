@@ -24,6 +24,8 @@ from .binding import (  # noqa: F401
     pattern_sizes,
     schedule_base_level,
     select_blocks,
+    select_blocks_device,
+    vote_accumulate_device,
     share_timesteps,
     sparse_attn_fwd,
     spatial_similarity,

@@ -138,6 +138,10 @@ def load_library():
         C.c_void_p, C.c_int64, C.c_void_p]
     lib.calibatt_anchor_split_plan.restype = C.c_int
     lib.calibatt_anchor_split_plan.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_int32), C.POINTER(C.c_int64)]
+    lib.calibatt_select_blocks_device.restype = C.c_int
+    lib.calibatt_select_blocks_device.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_double, C.c_void_p, C.c_void_p]
+    lib.calibatt_vote_accumulate_device.restype = C.c_int
+    lib.calibatt_vote_accumulate_device.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     lib.calibatt_strerror.restype = C.c_char_p
     lib.calibatt_strerror.argtypes = [C.c_int]
     lib.calibatt_version.restype = C.c_int
@@ -470,6 +474,47 @@ def block_energy(q, k, block_q: int, block_k: int, scale: float, out=None, strea
     if st != 0:
         raise CalibattError(st, "calibatt_block_energy")
     return out
+
+
+def select_blocks_device(energy, eps: float, out=None, stream=None):
+    """calibatt_select_blocks_device on a contiguous fp32 CUDA tensor [..., nbk]: uint8 CUDA mask of the
+    same shape (``out`` if given)."""
+    import torch
+
+    lib = load_library()
+    if not (energy.is_cuda and energy.dtype == torch.float32 and energy.is_contiguous() and energy.dim() >= 1):
+        raise ValueError("energy must be a contiguous fp32 CUDA tensor [..., nbk]")
+    if out is None:
+        out = torch.empty(energy.shape, dtype=torch.uint8, device=energy.device)
+    elif not (out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous() and out.shape == energy.shape):
+        raise ValueError("out must be a contiguous uint8 CUDA tensor of the energies' shape")
+    nbk = energy.shape[-1]
+    if stream is None:
+        stream = torch.cuda.current_stream(energy.device).cuda_stream
+    st = lib.calibatt_select_blocks_device(energy.data_ptr(), energy.numel() // max(nbk, 1), nbk, float(eps),
+                                           out.data_ptr(), C.c_void_p(stream))
+    if st != 0:
+        raise CalibattError(st, "calibatt_select_blocks_device")
+    return out
+
+
+def vote_accumulate_device(mask, counts, stream=None):
+    """calibatt_vote_accumulate_device: ``mask`` uint8 CUDA tensor of n entries, ``counts`` int16 CUDA
+    tensor of n entries holding uint16 counters (torch has no arithmetic on uint16; read them back with
+    ``counts.cpu().numpy().view(numpy.uint16)``)."""
+    import torch
+
+    lib = load_library()
+    if not (mask.is_cuda and mask.dtype == torch.uint8 and mask.is_contiguous()):
+        raise ValueError("mask must be a contiguous uint8 CUDA tensor")
+    if not (counts.is_cuda and counts.dtype == torch.int16 and counts.is_contiguous() and counts.numel() == mask.numel()):
+        raise ValueError("counts must be a contiguous int16 CUDA tensor with one entry per mask entry")
+    if stream is None:
+        stream = torch.cuda.current_stream(mask.device).cuda_stream
+    st = lib.calibatt_vote_accumulate_device(mask.data_ptr(), mask.numel(), counts.data_ptr(), C.c_void_p(stream))
+    if st != 0:
+        raise CalibattError(st, "calibatt_vote_accumulate_device")
+    return counts
 
 
 def select_blocks(energy, eps: float) -> np.ndarray:

@@ -11,6 +11,7 @@
 #include "attn_kernel_anchor.h"
 #include "attn_kernel_energy.h"
 #include "attn_kernel_similarity.h"
+#include "calibration_kernels.h"
 #include "attn_kernel_pipe.h"
 #include "attn_kernel_pp.h"
 #include "calibatt.h"
@@ -273,6 +274,28 @@ int launch_similarity(const uint16_t *q, const uint16_t *k, const int32_t *partn
 }
 
 }  // namespace
+
+extern "C" int calibatt_select_blocks_device(const float *energy, int64_t n_rows, int nbk, double eps, uint8_t *mask,
+                                             void *stream) {
+  if (!energy || !mask) return CALIBATT_ERR_NULL;
+  if (n_rows < 0 || nbk <= 0 || eps != eps) return CALIBATT_ERR_SHAPE;
+  if (nbk > SELECT_MAX_COLS) return CALIBATT_ERR_UNSUPPORTED;
+  if ((uintptr_t)energy & 3) return CALIBATT_ERR_SHAPE;
+  if (n_rows == 0) return CALIBATT_OK;
+  int P = 2;
+  while (P < nbk) P <<= 1;
+  const unsigned grid = (unsigned)std::min<long long>(n_rows, 1 << 16);
+  return launch_kernel(select_blocks_kernel, grid, SELECT_THREADS, P * 8, (hipStream_t)stream, energy,
+                       (long long)n_rows, nbk, P, eps, mask);
+}
+
+extern "C" int calibatt_vote_accumulate_device(const uint8_t *mask, int64_t n, uint16_t *counts, void *stream) {
+  if (!mask || !counts) return CALIBATT_ERR_NULL;
+  if (n < 0 || ((uintptr_t)counts & 1)) return CALIBATT_ERR_SHAPE;
+  if (n == 0) return CALIBATT_OK;
+  const unsigned grid = (unsigned)std::min<long long>((n + 255) / 256, 1 << 16);
+  return launch_kernel(vote_accumulate_kernel, grid, 256, 0, (hipStream_t)stream, mask, (long long)n, counts);
+}
 
 extern "C" int calibatt_spatial_similarity(const void *q, const void *k, int B, int H, int N, int D,
                                            const int32_t *partner, int n_tok, int row_len, float scale,

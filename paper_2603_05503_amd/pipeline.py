@@ -36,7 +36,7 @@ class Calibrator:
         self.H, self.N, self.D = H, N, D
         self.block_q, self.block_k = block_q, block_k
         self.geometry, self.anchors, self.rho, self.gamma = geometry, anchors, rho, gamma
-        self._counts: Dict[Hashable, np.ndarray] = {}   # uint16 per block: prompts that kept it
+        self._counts: Dict[Hashable, object] = {}       # CUDA tensor, uint16 per block: prompts that kept it
         self._n: Dict[Hashable, int] = {}
         self._scores: Dict[Hashable, List[np.ndarray]] = {}
         self._partner = None
@@ -46,11 +46,15 @@ class Calibrator:
         prompt) at the step/layer ``key``, with the energy threshold ``eps`` of that step."""
         import torch
 
+        # energy -> Eq. 6 -> one more vote per block, all on the device; the counters come back in finalize
         energy = _b.block_energy(q, k, self.block_q, self.block_k, scale)
-        masks = _b.select_blocks(energy.cpu().numpy(), eps)  # [B, H, nbq, nbk]
-        counts = self._counts.setdefault(key, np.zeros(masks.shape[1:], np.uint16))
+        masks = _b.select_blocks_device(energy, eps)  # [B, H, nbq, nbk]
+        if self._n.get(key, 0) + masks.shape[0] > 65535:
+            raise ValueError("at most 65535 prompts per key")
+        if key not in self._counts:
+            self._counts[key] = torch.zeros(masks.shape[1:], dtype=torch.int16, device=q.device)  # uint16 counters
         for b in range(masks.shape[0]):
-            _b.vote_accumulate(masks[b], counts)
+            _b.vote_accumulate_device(masks[b], self._counts[key])
         self._n[key] = self._n.get(key, 0) + masks.shape[0]
         if self.geometry is not None:
             F, Hs, Ws = self.geometry
@@ -62,7 +66,7 @@ class Calibrator:
     def finalize(self, merge_percentile: Optional[float] = None) -> Dict[Hashable, CalibrationResult]:
         out = {}
         for key, counts in self._counts.items():
-            mask = _b.vote_finish(counts, self._n[key], self.rho)
+            mask = _b.vote_finish(counts.cpu().numpy().view(np.uint16), self._n[key], self.rho)
             if merge_percentile is not None:
                 mask, _ = _b.merge_intervals(mask, merge_percentile)
             scores, flagged = None, []

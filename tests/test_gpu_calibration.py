@@ -213,3 +213,90 @@ def test_spatial_similarity_wan480_sampled(lib):
     for (b, h, f, i), w in zip(items, want):
         assert abs(cos[h, f * Hs + i] - w) <= 2e-3, (h, f, i, cos[h, f * Hs + i], w)
     assert abs(cos[1, 5 * Hs + 15] - 1.0) < 1e-5  # row 15 is an anchor: compared with itself
+
+
+# ---- Eq. 6 and the vote counters on the device ------------------------------------------------------
+
+def _energy_rows(seed, n_rows, nbk):
+    """Rows shaped like block energies (non-negative, summing to about 1) with the cases that decide
+    the order: exact ties, zeros, negative zeros, one dominant block, a row that never reaches eps."""
+    rng = np.random.default_rng(seed)
+    e = rng.random((n_rows, nbk)).astype(np.float32) ** 6
+    e /= e.sum(axis=1, keepdims=True)
+    e = e.astype(np.float32)
+    if n_rows > 6 and nbk > 4:
+        e[0, :] = np.float32(1.0 / nbk)                 # all equal: columns ascending
+        e[1, ::2] = e[1, 1::2][: e[1, ::2].size] if nbk % 2 == 0 else e[1, ::2]   # pairs of equal energies
+        e[2, :] = 0.0                                   # never reaches eps: everything kept
+        e[2, 1] = -0.0
+        e[3, :] = 0.0
+        e[3, nbk // 2] = 1.0                            # one block is enough
+        e[4, :] *= 0.5                                  # total 0.5 < eps
+        e[5, : nbk // 2] = 0.0                          # zeros in front
+        e[6, :] = np.float32(1e-30)                     # tiny values: the running sum is fp64
+        e[6, nbk - 1] = 0.9
+    return e
+
+
+@pytest.mark.parametrize("n_rows,nbk,eps", [(40, 256, 0.9), (33, 591, 0.84), (17, 350, 0.99), (9, 1, 0.5),
+                                            (12, 2, 0.7), (25, 100, 0.0), (7, 4096, 0.95), (10, 257, 1.5)])
+def test_select_blocks_device_is_bit_exact(lib, n_rows, nbk, eps):
+    """The device selection equals the oracle's (sequential fp64 sum in sorted order) and the host
+    routine's, entry by entry."""
+    import torch
+
+    print(f"device select n_rows={n_rows} nbk={nbk} eps={eps}", flush=True)
+    e = _energy_rows(90 + nbk, n_rows, nbk)
+    got = lib.select_blocks_device(torch.from_numpy(e).cuda(), eps)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    want = select_blocks(e, eps)
+    assert got.dtype == np.uint8 and got.shape == want.shape
+    assert (got == want).all()
+    assert (got == lib.select_blocks(e, eps)).all()
+
+
+def test_select_blocks_device_refuses_what_it_cannot_hold(lib):
+    import torch
+    from paper_2603_05503_amd.binding import CalibattError
+
+    with pytest.raises(CalibattError) as err:
+        lib.select_blocks_device(torch.zeros((2, 4097), dtype=torch.float32, device="cuda"), 0.9)
+    assert err.value.status == -3
+
+
+def test_vote_counters_on_the_device(lib):
+    """Counters after several prompts equal the host routine's; a full counter stays full."""
+    import torch
+
+    print("device vote counters", flush=True)
+    rng = np.random.default_rng(12)
+    n = 100_003
+    masks = (rng.random((5, n)) < 0.4).astype(np.uint8) * rng.integers(1, 255, (5, n)).astype(np.uint8)
+    host = np.zeros(n, np.uint16)
+    dev = torch.zeros(n, dtype=torch.int16, device="cuda")
+    for m in masks:
+        lib.vote_accumulate(m, host)
+        lib.vote_accumulate_device(torch.from_numpy(m).cuda(), dev)
+    torch.cuda.synchronize()
+    assert (dev.cpu().numpy().view(np.uint16) == host).all()
+    full = torch.from_numpy(np.array([65535, 65534, 0], np.uint16).view(np.int16)).cuda()
+    lib.vote_accumulate_device(torch.tensor([1, 1, 0], dtype=torch.uint8, device="cuda"), full)
+    torch.cuda.synchronize()
+    assert full.cpu().numpy().view(np.uint16).tolist() == [65535, 65535, 0]
+
+
+def test_device_chain_equals_host_chain_at_wan480_rows(lib):
+    """Energies of two heads at the Wan 480p length: the device selection of all 512 rows equals the
+    host selection of the same energies (both bit-exact routines of the same definition)."""
+    import torch
+
+    print("device select on kernel energies, N=32760", flush=True)
+    B, H, N, D = 1, 2, 32760, 128
+    q, k = _qk(404, B, H, N, D, 2.0)
+    E = lib.block_energy(to_dev(q), to_dev(k), 128, 128, 1 / math.sqrt(D))
+    got = lib.select_blocks_device(E, 0.9)
+    torch.cuda.synchronize()
+    want = lib.select_blocks(E.cpu().numpy(), 0.9)
+    assert (got.cpu().numpy() == want).all()
+    assert 0 < want.mean() < 1
