@@ -36,7 +36,7 @@ def test_fullsize_sampled_parity(lib, name, density):
 
     print(f"full size {name}", flush=True)
     wl = make_workload(name, density=density)
-    hp = lib.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, 3)
+    hp = lib.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, 4)  # the schedule bench.py times
     dp = hp.to_device()
     q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
     out = torch.empty_like(q)
@@ -88,7 +88,7 @@ def test_step_sweep_patterns(lib):
     built = []
     for layer, step in cases:
         mask, repeat, _ = sweep_pattern(layer, step, heads=4)
-        hp = lib.compile_pattern(mask, repeat, 4, wl.N, wl.block_q, wl.block_k, 3)
+        hp = lib.compile_pattern(mask, repeat, 4, wl.N, wl.block_q, wl.block_k, 4)  # the schedule bench.py times
         built.append((mask, repeat, hp.to_device(intervals=(step % 2 == 1))))
     outs = [torch.empty_like(q) for _ in cases]
     for (mask, repeat, dp), out in zip(built, outs):
