@@ -224,7 +224,7 @@ class HostPattern:
         return encode_intervals(self.row_ptr, self.col_idx)
 
 
-def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1) -> HostPattern:
+def compile_pattern(mask, repeat, H, N, block_q, block_k, order=4) -> HostPattern:
     lib = load_library()
     if min(H, N, block_q, block_k) <= 0:
         raise CalibattError(-2, "calibatt_compile_pattern")
