@@ -411,6 +411,32 @@ int calibatt_block_energy(const void *q, const void *k, float *energy, int B, in
                           int block_q, int block_k, float scale, void *stream);
 
 /*
+ * The same energies (Eq. 5) in one pass over the keys instead of two, for
+ * callers that bring a workspace: while a row's softmax statistics are still
+ * running, the logarithm of the mass it puts on each key block is parked in
+ * the workspace (it needs no reference maximum), and turned into the block's
+ * share once the row's log-sum-exp is known.  Half the matrix work; results
+ * agree with calibatt_block_energy within the energies' tolerance (not bit for
+ * bit), same bits on every run.
+ *   workspace        DEVICE, 4-byte aligned, owned by the caller, contents
+ *                    irrelevant before and undefined after; used by this call's
+ *                    kernel only (successive calls on one stream may share it,
+ *                    calls that may overlap may not).
+ *   workspace_bytes  any size from one slice (ceil(N/block_k) * block_q * 4
+ *                    bytes) up: the kernel runs as many workgroups as there
+ *                    are slices, the GPU holds at a time, and there are query
+ *                    blocks.  calibatt_block_energy_workspace_bytes (host, no
+ *                    GPU needed) returns 1024 slices, enough for every
+ *                    supported shape on a 256-CU part.
+ * Other arguments, supported shapes and errors as calibatt_block_energy, plus
+ * BUFFER_TOO_SMALL (less than one slice).
+ */
+int calibatt_block_energy_workspace_bytes(int N, int block_q, int block_k, int64_t *bytes);
+int calibatt_block_energy_onepass(const void *q, const void *k, float *energy, int B, int H, int N, int D,
+                                  int block_q, int block_k, float scale, void *workspace,
+                                  int64_t workspace_bytes, void *stream);
+
+/*
  * calibatt_select_blocks (Eq. 6): for each of n_rows block-rows of nbk
  * energies, keep the smallest set of blocks whose energies sum to at least
  * eps: sort descending (equal energies: lower column first), take the shortest

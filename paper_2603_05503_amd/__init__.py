@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     anchor_map,
     anchor_partner,
     block_energy,
+    block_energy_workspace_bytes,
     compile_pattern,
     encode_intervals,
     epsilon_schedule,

@@ -138,6 +138,11 @@ def load_library():
         C.c_void_p, C.c_int64, C.c_void_p]
     lib.calibatt_anchor_split_plan.restype = C.c_int
     lib.calibatt_anchor_split_plan.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_int32), C.POINTER(C.c_int64)]
+    lib.calibatt_block_energy_workspace_bytes.restype = C.c_int
+    lib.calibatt_block_energy_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int64)]
+    lib.calibatt_block_energy_onepass.restype = C.c_int
+    lib.calibatt_block_energy_onepass.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [
+        C.c_float, C.c_void_p, C.c_int64, C.c_void_p]
     lib.calibatt_select_blocks_device.restype = C.c_int
     lib.calibatt_select_blocks_device.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_double, C.c_void_p, C.c_void_p]
     lib.calibatt_vote_accumulate_device.restype = C.c_int
@@ -450,9 +455,19 @@ def anchor_attn_fwd(q, k, v, out, head_ids, amap: DeviceAnchorMap, scale: float,
     return out
 
 
-def block_energy(q, k, block_q: int, block_k: int, scale: float, out=None, stream=None):
+def block_energy_workspace_bytes(N: int, block_q: int, block_k: int) -> int:
+    lib = load_library()
+    n = C.c_int64(0)
+    st = lib.calibatt_block_energy_workspace_bytes(N, block_q, block_k, C.byref(n))
+    if st != 0:
+        raise CalibattError(st, "calibatt_block_energy_workspace_bytes")
+    return n.value
+
+
+def block_energy(q, k, block_q: int, block_k: int, scale: float, out=None, stream=None, workspace=None):
     """calibatt_block_energy on torch bf16 CUDA tensors [B, H, N, D]; returns the fp32 CUDA tensor
-    [B, H, ceil(N/block_q), ceil(N/block_k)] (``out`` if given)."""
+    [B, H, ceil(N/block_q), ceil(N/block_k)] (``out`` if given).  ``workspace`` (a contiguous CUDA
+    tensor, see ``block_energy_workspace_bytes``) selects calibatt_block_energy_onepass."""
     import torch
 
     lib = load_library()
@@ -469,8 +484,15 @@ def block_energy(q, k, block_q: int, block_k: int, scale: float, out=None, strea
         raise ValueError(f"out must be a contiguous fp32 CUDA tensor of shape {shape}")
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
-    st = lib.calibatt_block_energy(q.data_ptr(), k.data_ptr(), out.data_ptr(), B, H, N, D, block_q, block_k,
-                                   float(scale), C.c_void_p(stream))
+    if workspace is not None:
+        if not (workspace.is_cuda and workspace.is_contiguous() and workspace.device == q.device):
+            raise ValueError("workspace must be a contiguous CUDA tensor on the tensors' device")
+        st = lib.calibatt_block_energy_onepass(q.data_ptr(), k.data_ptr(), out.data_ptr(), B, H, N, D, block_q, block_k,
+                                               float(scale), workspace.data_ptr(),
+                                               workspace.numel() * workspace.element_size(), C.c_void_p(stream))
+    else:
+        st = lib.calibatt_block_energy(q.data_ptr(), k.data_ptr(), out.data_ptr(), B, H, N, D, block_q, block_k,
+                                       float(scale), C.c_void_p(stream))
     if st != 0:
         raise CalibattError(st, "calibatt_block_energy")
     return out

@@ -198,11 +198,12 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
   return a + b;
 }
 
-// Sum of x over the 64 lanes of the wave, delivered to every lane, as a fixed
-// butterfly (the same order of additions in every run): xor 1, 2 (quad
-// permutes), 4 (half-row mirror), 8 (row mirror) inside rows of 16 lanes, then
-// the 16-lane and 32-lane swaps across rows.
-__device__ __forceinline__ float wave_sum(float x) {
+// Sum of x over the 32 lanes of this lane's half of the wave (half_wave_sum) or
+// over all 64 lanes (wave_sum), delivered to every lane, as a fixed butterfly
+// (the same order of additions in every run): xor 1, 2 (quad permutes), 4
+// (half-row mirror), 8 (row mirror) inside rows of 16 lanes, then the 16-lane
+// and, for the whole wave, the 32-lane swap across rows.
+__device__ __forceinline__ float half_wave_sum(float x) {
   auto dpp = [](float v, auto ctrl) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value,
                                                                  0xf, 0xf, false));
@@ -213,7 +214,8 @@ __device__ __forceinline__ float wave_sum(float x) {
   x += dpp(x, std::integral_constant<int, 0x140>{});  // row_mirror
   float a = x, b = x;
   asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-  return sum_with_other_half(a + b);
+  return a + b;
 }
+__device__ __forceinline__ float wave_sum(float x) { return sum_with_other_half(half_wave_sum(x)); }
 
 }  // namespace calibatt_dev

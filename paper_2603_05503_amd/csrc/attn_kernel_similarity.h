@@ -11,9 +11,12 @@
 //
 // Kernel 1: one workgroup per (batch, head, 128 tokens).  A lane owns a token
 // AND its partner: two query operands, two score tiles per key tile
-// (RowBlock::scores twice), two passes over all keys like the energy kernel
-// (pass 1: row max / row sum of both; pass 2: the three sums).  Writes the
-// normalised triple of every token.
+// (RowBlock::scores twice), ONE pass over all keys: the row sums of both and
+// the three sums of products are kept relative to the running maxima of the
+// two queries and rescaled when a maximum moves (the sums of products by the
+// product of the two factors), exactly as an online softmax keeps its row sum;
+// the normalisers divide out at the end.  Writes the normalised triple of
+// every token.
 // Kernel 2: one wavefront per (batch, head) adds the triples of each spatial
 // row, forms the cosine and averages over rows in a fixed order.
 #pragma once
@@ -70,8 +73,9 @@ __global__ __launch_bounds__(SIM_BQ * 2, 2) void pair_similarity_kernel(
   float m_t = -INFINITY, l_t = 0.f, m_a = -INFINITY, l_a = 0.f;
   float dot = 0.f, nt = 0.f, na = 0.f;
 
-  // running max / sum of one query over one tile of raw products (multiplier sc_t still to apply)
-  auto fold_stats = [&](const f32x16 (&s)[KB], float sc_t, float &m_run, float &l_run) {
+  // largest scaled logit of one query over one tile of raw products (multiplier sc_t still to apply),
+  // folded into the running maximum; returns the factor 2^(old max - new max) for what was summed so far
+  auto fold_max = [&](const f32x16 (&s)[KB], float sc_t, float &m_run) {
     float m_loc;
     if (sc_t >= 0.f) {
       m_loc = -INFINITY;
@@ -87,13 +91,9 @@ __global__ __launch_bounds__(SIM_BQ * 2, 2) void pair_similarity_kernel(
         for (int v = 0; v < 16; ++v) m_loc = fminf(m_loc, s[kb][v]);
     }
     const float m_new = fmaxf(m_run, max_with_other_half(m_loc * sc_t));
-    float psum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], sc_t, -m_new));
-    l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
     m_run = m_new;
+    return alpha;
   };
   // keys >= N of the ragged last tile to -inf; scales the tile up front
   auto mask_tail = [&](f32x16 (&s)[KB], int c) {
@@ -107,38 +107,41 @@ __global__ __launch_bounds__(SIM_BQ * 2, 2) void pair_similarity_kernel(
       }
   };
 
-  // Tiles of both passes form one sequence t = pass * nbk + c; tile t sits in buffer t & 1.
-  const int n_steps = 2 * p.nbk;
-  for (int t = 0; t < n_steps; ++t) {
-    const bool second = t >= p.nbk;
-    const int c = second ? t - p.nbk : t;
+  // One pass: all five sums are kept relative to the running maxima of the two queries and
+  // rescaled when a maximum moves, like the row sum of an online softmax.  Tile c sits in buffer c & 1.
+  for (int c = 0; c < p.nbk; ++c) {
     wait_vmem<0>();
-    __syncthreads();  // tile t has landed for every wave; everyone is done with the other buffer
-    if (t + 1 < n_steps) rb.issue_k_at(Kres, c + 1 < p.nbk ? c + 1 : 0, ((t + 1) & 1) * TILE_BYTES);
+    __syncthreads();  // tile c has landed for every wave; everyone is done with the other buffer
+    if (c + 1 < p.nbk) rb.issue_k_at(Kres, c + 1, ((c + 1) & 1) * TILE_BYTES);
     f32x16 s_t[KB], s_a[KB];
-    rb.scores((t & 1) * TILE_BYTES, s_t, q_t);
-    rb.scores((t & 1) * TILE_BYTES, s_a, q_a);
+    rb.scores((c & 1) * TILE_BYTES, s_t, q_t);
+    rb.scores((c & 1) * TILE_BYTES, s_a, q_a);
     float sc_t = sc;
     if (ragged && c == p.nbk - 1) {
       mask_tail(s_t, c);
       mask_tail(s_a, c);
       sc_t = 1.0f;
     }
-    if (!second) {
-      fold_stats(s_t, sc_t, m_t, l_t);
-      fold_stats(s_a, sc_t, m_a, l_a);
-    } else {
+    const float alpha_t = fold_max(s_t, sc_t, m_t);
+    const float alpha_a = fold_max(s_a, sc_t, m_a);
+    float sum_t = 0.f, sum_a = 0.f, sum_ta = 0.f, sum_tt = 0.f, sum_aa = 0.f;
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float et = __builtin_amdgcn_exp2f(__builtin_fmaf(s_t[kb][v], sc_t, -m_t));
-          const float ea = __builtin_amdgcn_exp2f(__builtin_fmaf(s_a[kb][v], sc_t, -m_a));
-          dot = __builtin_fmaf(et, ea, dot);
-          nt = __builtin_fmaf(et, et, nt);
-          na = __builtin_fmaf(ea, ea, na);
-        }
-    }
+      for (int v = 0; v < 16; ++v) {
+        const float et = __builtin_amdgcn_exp2f(__builtin_fmaf(s_t[kb][v], sc_t, -m_t));
+        const float ea = __builtin_amdgcn_exp2f(__builtin_fmaf(s_a[kb][v], sc_t, -m_a));
+        sum_t += et;
+        sum_a += ea;
+        sum_ta = __builtin_fmaf(et, ea, sum_ta);
+        sum_tt = __builtin_fmaf(et, et, sum_tt);
+        sum_aa = __builtin_fmaf(ea, ea, sum_aa);
+      }
+    l_t = __builtin_fmaf(l_t, alpha_t, sum_t);
+    l_a = __builtin_fmaf(l_a, alpha_a, sum_a);
+    dot = __builtin_fmaf(dot, alpha_t * alpha_a, sum_ta);
+    nt = __builtin_fmaf(nt, alpha_t * alpha_t, sum_tt);
+    na = __builtin_fmaf(na, alpha_a * alpha_a, sum_aa);
   }
   const float wt = 1.0f / sum_with_other_half(l_t);
   const float wa = 1.0f / sum_with_other_half(l_a);

@@ -257,6 +257,37 @@ int launch_energy(const uint16_t *q, const uint16_t *k, float *energy, const Ene
   return launch_kernel(kernel, (unsigned)grid, BQ * 2, (int)smem, stream, q, k, energy, p);
 }
 
+// One-pass energy kernel: as many persistent workgroups as the device holds at a time, the
+// workspace has slices for, and there are units.
+template <int D, int BQ, int BK>
+int launch_energy_onepass(const uint16_t *q, const uint16_t *k, float *energy, const EnergyDims &p, float *workspace,
+                          long long workspace_bytes, hipStream_t stream) {
+  const long long units = (long long)p.B * p.H * p.nbq;
+  const long long smem = EnergyLds<D, BQ, BK>::bytes(p.nbk);
+  if (smem > ENERGY_MAX_LDS) return CALIBATT_ERR_UNSUPPORTED;
+  const long long slice = (long long)p.nbk * BQ * 4;
+  if (workspace_bytes < slice) return CALIBATT_ERR_BUFFER_TOO_SMALL;
+  auto kernel = block_energy_onepass_kernel<D, BQ, BK>;
+  static bool ready[64];
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CALIBATT_ERR_LAUNCH;
+  if (!ready[dev]) {
+    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ENERGY_MAX_LDS) !=
+        hipSuccess)
+      return CALIBATT_ERR_LAUNCH;
+    ready[dev] = true;
+  }
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kernel, BQ * 2, (size_t)smem) != hipSuccess ||
+      cus <= 0 || per_cu <= 0)
+    return CALIBATT_ERR_LAUNCH;
+  EnergyOnePassDims pp;
+  pp.e = p;
+  pp.n_wg = (int)std::min<long long>({units, (long long)cus * per_cu, workspace_bytes / slice, 1 << 20});
+  pp.xcds = pp.n_wg >= ENERGY_XCDS ? ENERGY_XCDS : 1;
+  return launch_kernel(kernel, (unsigned)pp.n_wg, BQ * 2, (int)smem, stream, q, k, energy, workspace, pp);
+}
+
 template <int D>
 int launch_similarity(const uint16_t *q, const uint16_t *k, const int32_t *partner, float *triples, float *score,
                       const SimilarityDims &p, hipStream_t stream) {
@@ -338,6 +369,47 @@ extern "C" int calibatt_block_energy(const void *q, const void *k, float *energy
   hipStream_t s = (hipStream_t)stream;
 #define CALIBATT_CASE(d, bq, bk) \
   if (D == d && block_q == bq && block_k == bk) return launch_energy<d, bq, bk>(qq, kk, energy, p, s);
+  CALIBATT_CASE(128, 128, 128)
+  CALIBATT_CASE(128, 128, 64)
+  CALIBATT_CASE(128, 64, 128)
+  CALIBATT_CASE(128, 64, 64)
+  CALIBATT_CASE(64, 128, 128)
+  CALIBATT_CASE(64, 128, 64)
+  CALIBATT_CASE(64, 64, 128)
+  CALIBATT_CASE(64, 64, 64)
+#undef CALIBATT_CASE
+  return CALIBATT_ERR_UNSUPPORTED;
+}
+
+extern "C" int calibatt_block_energy_workspace_bytes(int N, int block_q, int block_k, int64_t *bytes) {
+  if (!bytes) return CALIBATT_ERR_NULL;
+  if (N <= 0 || block_q <= 0 || block_k <= 0) return CALIBATT_ERR_SHAPE;
+  if (!(block_q == 64 || block_q == 128) || !(block_k == 64 || block_k == 128)) return CALIBATT_ERR_UNSUPPORTED;
+  *bytes = 1024LL * ((N + block_k - 1) / block_k) * block_q * 4;
+  return CALIBATT_OK;
+}
+
+extern "C" int calibatt_block_energy_onepass(const void *q, const void *k, float *energy, int B, int H, int N, int D,
+                                             int block_q, int block_k, float scale, void *workspace,
+                                             int64_t workspace_bytes, void *stream) {
+  if (!q || !k || !energy || !workspace) return CALIBATT_ERR_NULL;
+  if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || block_q <= 0 || block_k <= 0 || workspace_bytes < 0)
+    return CALIBATT_ERR_SHAPE;
+  if (!(D == 64 || D == 128) || !(block_q == 64 || block_q == 128) || !(block_k == 64 || block_k == 128))
+    return CALIBATT_ERR_UNSUPPORTED;
+  if ((size_t)B * H * N * D > 0x7fffffff00ULL || ((uintptr_t)workspace & 3)) return CALIBATT_ERR_SHAPE;
+  EnergyDims p;
+  p.B = B;
+  p.H = H;
+  p.N = N;
+  p.nbq = (N + block_q - 1) / block_q;
+  p.nbk = (N + block_k - 1) / block_k;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  const uint16_t *qq = (const uint16_t *)q, *kk = (const uint16_t *)k;
+  hipStream_t s = (hipStream_t)stream;
+#define CALIBATT_CASE(d, bq, bk)                        \
+  if (D == d && block_q == bq && block_k == bk)         \
+    return launch_energy_onepass<d, bq, bk>(qq, kk, energy, p, (float *)workspace, workspace_bytes, s);
   CALIBATT_CASE(128, 128, 128)
   CALIBATT_CASE(128, 128, 64)
   CALIBATT_CASE(128, 64, 128)

@@ -40,6 +40,7 @@ class Calibrator:
         self._n: Dict[Hashable, int] = {}
         self._scores: Dict[Hashable, List[np.ndarray]] = {}
         self._partner = None
+        self._energy_workspace = None   # of the one-pass energy kernel; calls are issued on one stream
 
     def observe(self, key: Hashable, q, k, eps: float, scale: float) -> None:
         """One dense forward's q, k ([B, H, N, D] bf16 CUDA tensors; every batch element counts as a
@@ -47,7 +48,10 @@ class Calibrator:
         import torch
 
         # energy -> Eq. 6 -> one more vote per block, all on the device; the counters come back in finalize
-        energy = _b.block_energy(q, k, self.block_q, self.block_k, scale)
+        if self._energy_workspace is None or self._energy_workspace.device != q.device:
+            nbytes = _b.block_energy_workspace_bytes(self.N, self.block_q, self.block_k)
+            self._energy_workspace = torch.empty(nbytes // 4, dtype=torch.float32, device=q.device)
+        energy = _b.block_energy(q, k, self.block_q, self.block_k, scale, workspace=self._energy_workspace)
         masks = _b.select_blocks_device(energy, eps)  # [B, H, nbq, nbk]
         if self._n.get(key, 0) + masks.shape[0] > 65535:
             raise ValueError("at most 65535 prompts per key")

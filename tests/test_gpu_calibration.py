@@ -42,15 +42,32 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("B,H,N,D,bq,bk,gain,scale", CASES)
-def test_block_energy_parity(lib, B, H, N, D, bq, bk, gain, scale):
+def _workspace(lib, N, bq, bk, slices=None):
+    """Workspace of the one-pass kernel, NaN-filled: what it reads back it must have written.
+    slices=None: the recommended size."""
     import torch
 
-    print(f"energy parity B={B} H={H} N={N} D={D} bq={bq} bk={bk} gain={gain} scale={scale}", flush=True)
+    nbytes = lib.block_energy_workspace_bytes(N, bq, bk)
+    one = -(-N // bk) * bq * 4
+    assert nbytes == 1024 * one
+    if slices is not None:
+        nbytes = slices * one
+    return torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+
+
+# passes: 2 = calibatt_block_energy; 1 = calibatt_block_energy_onepass with the recommended workspace;
+# (1, n) = the same with n slices only (n persistent workgroups walk all query blocks)
+@pytest.mark.parametrize("passes", [2, 1, (1, 1), (1, 11)], ids=["two-pass", "one-pass", "one-pass-1wg", "one-pass-11wg"])
+@pytest.mark.parametrize("B,H,N,D,bq,bk,gain,scale", CASES)
+def test_block_energy_parity(lib, B, H, N, D, bq, bk, gain, scale, passes):
+    import torch
+
+    print(f"energy parity B={B} H={H} N={N} D={D} bq={bq} bk={bk} gain={gain} scale={scale} passes={passes}", flush=True)
     q, k = _qk(31 + N + D + bq + bk, B, H, N, D, gain)
     scale = 1 / math.sqrt(D) if scale is None else scale
     tq, tk = to_dev(q), to_dev(k)
-    E = lib.block_energy(tq, tk, bq, bk, scale)
+    ws = None if passes == 2 else _workspace(lib, N, bq, bk, None if passes == 1 else passes[1])
+    E = lib.block_energy(tq, tk, bq, bk, scale, workspace=ws)
     torch.cuda.synchronize()
     got = E.cpu().numpy().astype(np.float64)
     want = block_energy(q, k, scale, bq, bk)
@@ -60,7 +77,7 @@ def test_block_energy_parity(lib, B, H, N, D, bq, bk, gain, scale):
     np.testing.assert_allclose(got.sum(axis=-1), 1.0, rtol=0, atol=2e-4)
     # same bits on a second run into a poisoned buffer
     E2 = torch.full_like(E, float("nan"))
-    lib.block_energy(tq, tk, bq, bk, scale, out=E2)
+    lib.block_energy(tq, tk, bq, bk, scale, out=E2, workspace=ws)
     torch.cuda.synchronize()
     assert torch.equal(E, E2)
 
@@ -77,16 +94,18 @@ def test_uniform_attention_gives_block_sizes(lib):
     np.testing.assert_allclose(E[0, 0], np.broadcast_to(sizes, E[0, 0].shape), rtol=1e-5)
 
 
-def test_wan480_sampled_parity(lib):
+@pytest.mark.parametrize("passes", [2, 1], ids=["two-pass", "one-pass"])
+def test_wan480_sampled_parity(lib, passes):
     """Full Wan-480p sequence length on a few heads with positionally structured
     q, k (the bench workload's recipe): sampled block-rows against the oracle,
     every block-row sums to 1."""
     import torch
     from workloads import make_workload
 
-    print("energy wan480", flush=True)
+    print(f"energy wan480 passes={passes}", flush=True)
     wl = make_workload("wan480", heads=3, qk_gain=1.5)
-    E = lib.block_energy(to_dev(wl.q), to_dev(wl.k), wl.block_q, wl.block_k, wl.scale)
+    ws = _workspace(lib, wl.N, wl.block_q, wl.block_k) if passes == 1 else None
+    E = lib.block_energy(to_dev(wl.q), to_dev(wl.k), wl.block_q, wl.block_k, wl.scale, workspace=ws)
     torch.cuda.synchronize()
     got = E.cpu().numpy().astype(np.float64)
     assert got.shape == (1, 3, wl.nbq, wl.nbk) and np.isfinite(got).all()
@@ -300,3 +319,14 @@ def test_device_chain_equals_host_chain_at_wan480_rows(lib):
     want = lib.select_blocks(E.cpu().numpy(), 0.9)
     assert (got.cpu().numpy() == want).all()
     assert 0 < want.mean() < 1
+
+
+def test_onepass_workspace_too_small_is_refused(lib):
+    import torch
+    from paper_2603_05503_amd.binding import CalibattError
+
+    q, k = _qk(3, 1, 1, 300, 64)
+    ws = torch.empty(5 * 64 - 1, dtype=torch.float32, device="cuda")  # one float short of a slice (5 key blocks x 64 rows)
+    with pytest.raises(CalibattError) as err:
+        lib.block_energy(to_dev(q), to_dev(k), 64, 64, 0.1, workspace=ws)
+    assert err.value.status == -7
