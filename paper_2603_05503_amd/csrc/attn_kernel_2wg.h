@@ -188,14 +188,15 @@ struct RowBlock {
     float sc_t = sc;  // multiplier still to be applied to s_acc
     if (c == nbk - 1 && (N % BK) != 0) {
       // ragged last block: scale now, put keys >= N at -inf, continue with multiplier 1
-      const int key0 = c * BK + 8 * g;
+      int limit = N - c * BK - 8 * g;  // this lane's key offsets below `limit` exist
+      // Opaque to the optimiser: hoisted out of the tile loop, the 64 comparisons below would be
+      // evaluated for every row block and their masks would hold 128 scalar registers throughout.
+      asm volatile("" : "+v"(limit));
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
-          s_acc[kb][v] = key < N ? s_acc[kb][v] * sc : -INFINITY;
-        }
+        for (int v = 0; v < 16; ++v)
+          s_acc[kb][v] = 32 * kb + 16 * (v >> 3) + (v & 7) < limit ? s_acc[kb][v] * sc : -INFINITY;
       sc_t = 1.0f;
     }
     float m_loc;

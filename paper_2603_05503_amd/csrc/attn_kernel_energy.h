@@ -82,14 +82,13 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void block_energy_kern
     // tile is scaled up front so that its keys >= N can sit at -inf (multiplier 1 from then on).
     float sc_t = sc;
     if (ragged && c == p.nbk - 1) {
-      const int key0 = c * BK + 8 * rb.g;
+      int limit = N - c * BK - 8 * rb.g;  // this lane's key offsets below `limit` exist
+      asm volatile("" : "+v"(limit));      // keeps the comparisons (and their 64 masks) inside this branch
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
-          s[kb][v] = key < N ? s[kb][v] * sc : -INFINITY;
-        }
+        for (int v = 0; v < 16; ++v)
+          s[kb][v] = 32 * kb + 16 * (v >> 3) + (v & 7) < limit ? s[kb][v] * sc : -INFINITY;
       sc_t = 1.0f;
     }
     if (!second) {
@@ -208,14 +207,13 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void block_energy_onep
       rb.scores((c & 1) * TILE_BYTES, s);
       float sc_t = sc;
       if (ragged && c == p.nbk - 1) {  // keys >= N sit at -inf; the tile is scaled up front, multiplier 1 from then on
-        const int key0 = c * BK + 8 * rb.g;
+        int limit = N - c * BK - 8 * rb.g;  // this lane's key offsets below `limit` exist
+        asm volatile("" : "+v"(limit));      // keeps the comparisons (and their 64 masks) inside this branch
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
-            s[kb][v] = key < N ? s[kb][v] * sc : -INFINITY;
-          }
+          for (int v = 0; v < 16; ++v)
+            s[kb][v] = 32 * kb + 16 * (v >> 3) + (v & 7) < limit ? s[kb][v] * sc : -INFINITY;
         sc_t = 1.0f;
       }
       float m_loc;

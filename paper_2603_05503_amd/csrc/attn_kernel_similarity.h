@@ -97,14 +97,13 @@ __global__ __launch_bounds__(SIM_BQ * 2, 2) void pair_similarity_kernel(
   };
   // keys >= N of the ragged last tile to -inf; scales the tile up front
   auto mask_tail = [&](f32x16 (&s)[KB], int c) {
-    const int key0 = c * BK + 8 * rb.g;
+    int limit = N - c * BK - 8 * rb.g;  // this lane's key offsets below `limit` exist
+    asm volatile("" : "+v"(limit));      // keeps the comparisons (and their 64 masks) out of the tile loop's prologue
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = key0 + 32 * kb + 16 * (v >> 3) + (v & 7);
-        s[kb][v] = key < N ? s[kb][v] * sc : -INFINITY;
-      }
+      for (int v = 0; v < 16; ++v)
+        s[kb][v] = 32 * kb + 16 * (v >> 3) + (v & 7) < limit ? s[kb][v] * sc : -INFINITY;
   };
 
   // One pass: all five sums are kept relative to the running maxima of the two queries and
