@@ -16,15 +16,17 @@
  * Both forwards have a *_strided variant for tensors that are not packed.
  *
  * The calibration stage (Section 3.2-3.3) that produces the masks and the
- * flags: calibatt_block_energy() and calibatt_spatial_similarity() on the GPU,
- * calibatt_select_blocks(), calibatt_vote_*(), calibatt_epsilon_schedule() on
- * the host.  Skip-list tools of the supplement (Sections A.2, A.3):
+ * flags: calibatt_block_energy() / calibatt_block_energy_onepass() and
+ * calibatt_spatial_similarity() on the GPU; calibatt_select_blocks() and the
+ * vote counters on the host or, as *_device, on the GPU;
+ * calibatt_epsilon_schedule() on the host.  Skip-list tools of the supplement (Sections A.2, A.3):
  * calibatt_encode_intervals() (a compact form of the index lists that the
  * forward reads directly), calibatt_merge_intervals(),
  * calibatt_share_timesteps().
  *
  * Plain C, no exceptions cross the boundary, no global state is kept between
- * calls, every buffer is owned by the caller.  All functions return a
+ * calls, every buffer is owned by the caller; the library allocates no device
+ * memory (scratch comes in through workspace arguments).  All functions return a
  * calibatt_status (0 = success, negative = error) unless stated otherwise.
  */
 #ifndef CALIBATT_H

@@ -265,4 +265,4 @@ extern "C" const char *calibatt_strerror(int status) {
   }
 }
 
-extern "C" int calibatt_version(void) { return 100; }
+extern "C" int calibatt_version(void) { return 200; }
