@@ -330,3 +330,20 @@ def test_onepass_workspace_too_small_is_refused(lib):
     with pytest.raises(CalibattError) as err:
         lib.block_energy(to_dev(q), to_dev(k), 64, 64, 0.1, workspace=ws)
     assert err.value.status == -7
+
+
+def test_select_blocks_device_tolerates_nan(lib):
+    """Energies that are not numbers have no defined order, but the call still ends and writes a mask
+    of zeros and ones (the header's promise); the rows without NaN are unaffected."""
+    import torch
+
+    e = _energy_rows(7, 12, 200)
+    bad = e.copy()
+    bad[3, 17] = np.nan
+    bad[8, :] = np.nan
+    got = lib.select_blocks_device(torch.from_numpy(bad).cuda(), 0.9)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert set(np.unique(got)) <= {0, 1}
+    clean = [r for r in range(12) if r not in (3, 8)]
+    assert (got[clean] == select_blocks(e, 0.9)[clean]).all()
