@@ -216,30 +216,43 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) void block_energy_onep
             s[kb][v] = 32 * kb + 16 * (v >> 3) + (v & 7) < limit ? s[kb][v] * sc : -INFINITY;
         sc_t = 1.0f;
       }
-      float m_loc;
-      if (sc_t >= 0.f) {
-        m_loc = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) m_loc = fmaxf(m_loc, s[kb][v]);
-      } else {
-        m_loc = INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) m_loc = fminf(m_loc, s[kb][v]);
-      }
-      const float m_new = fmaxf(m_run, max_with_other_half(m_loc * sc_t));
+      // The reference m_run of the exponentials only has to keep them in range, it need not be the
+      // maximum: the tile is first summed against the reference as it stands, and only if some
+      // lane's sum leaves the safe range (always on the first tile, where the reference is -inf)
+      // does the wave look for the tile's maximum, move the reference and sum again.  The sums
+      // stay below 2^100 per tile, so the row sum cannot overflow.
       float psum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], sc_t, -m_new));
-      l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum;
-      m_run = m_new;
+        for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], sc_t, -m_run));
+      if (__any(!(psum < 0x1p100f))) {
+        float m_loc;
+        if (sc_t >= 0.f) {
+          m_loc = -INFINITY;
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) m_loc = fmaxf(m_loc, s[kb][v]);
+        } else {
+          m_loc = INFINITY;
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) m_loc = fminf(m_loc, s[kb][v]);
+        }
+        const float m_new = fmaxf(m_run, max_with_other_half(m_loc * sc_t));
+        psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], sc_t, -m_new));
+        l_run *= __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
+        m_run = m_new;
+      }
+      l_run += psum;
       // log2 of the row's mass on this block (-inf when it underflowed: the block then counts as 0)
-      t_prev = m_new + __builtin_amdgcn_logf(sum_with_other_half(psum));
+      t_prev = m_run + __builtin_amdgcn_logf(sum_with_other_half(psum));
     }
     if (((p.nbk - 1) & 1) == rb.g) mine[(size_t)(p.nbk - 1) * BQ] = t_prev;
     const float lse2 = m_run + __builtin_amdgcn_logf(sum_with_other_half(l_run));
