@@ -104,3 +104,51 @@ def test_step_sweep_patterns(lib):
         for (b, h, r), w in zip(items, want):
             g = bits_to_f64(got[b, h, r * wl.block_q : r * wl.block_q + w.shape[0]])
             assert np.abs(g - w).max() <= MAX_ABS and np.abs(g - w).mean() <= MEAN_ABS, (h, r)
+
+
+def test_mochi_shape_workspace_paths_agree_with_the_plain_ones():
+    """Mochi's sequence (44 520 video + 256 text tokens, 350 key blocks, ragged tail) through the
+    two calls that take a workspace: the anchor forward with the key-range split against the plain
+    one (same receivers, values within the forward's tolerance), the one-pass block energy against
+    the two-pass kernel (rtol 2e-3 + 2e-7, rows summing to 1).  The plain calls are checked against
+    the oracle elsewhere; this covers the split logic at a real shape: text tokens, 350 = 8 x 43 + 6
+    key tiles, units that do not fill whole rounds."""
+    import math
+
+    import torch
+
+    import paper_2603_05503_amd as lib
+    from workloads import CONFIGS
+
+    print("mochi shape: workspace paths", flush=True)
+    geom = CONFIGS["mochi"]["geom"]
+    F, Hs, Ws = geom.frames, geom.rows, geom.cols
+    N, D, H = geom.n_tokens, 128, 3
+    assert N == 44776
+    rng = np.random.default_rng(31)
+    from workloads import f32_to_bf16_bits
+    q, k, v = (to_dev(f32_to_bf16_bits((1.5 * rng.standard_normal((1, H, N, D))).astype(np.float32))) for _ in range(3))
+    scale = 1 / math.sqrt(D)
+    heads = torch.arange(H, dtype=torch.int32, device="cuda")
+    for anchors in (1, 5):
+        amap = lib.anchor_map(N, F, Hs, Ws, anchors).to_device()
+        n_split, nbytes = lib.anchor_split_plan(1, N, D, H, amap.n_q)
+        assert n_split > 1
+        ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        plain, split = torch.empty_like(q), torch.empty_like(q)
+        lib.anchor_attn_fwd(q, k, v, plain, heads, amap, scale)
+        lib.anchor_attn_fwd(q, k, v, split, heads, amap, scale, workspace=ws)
+        torch.cuda.synchronize()
+        a, b = bits_to_f64(from_dev(plain)), bits_to_f64(from_dev(split))
+        assert np.isfinite(b).all()
+        d = np.abs(a - b)
+        print(f"  k={anchors}: {n_split} parts, max_abs {d.max():.3e} mean_abs {d.mean():.3e}", flush=True)
+        assert d.max() <= MAX_ABS and d.mean() <= MEAN_ABS
+    ws = torch.full((lib.block_energy_workspace_bytes(N, 128, 128) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    two = lib.block_energy(q, k, 128, 128, scale)
+    one = lib.block_energy(q, k, 128, 128, scale, workspace=ws)
+    torch.cuda.synchronize()
+    two, one = two.cpu().numpy().astype(np.float64), one.cpu().numpy().astype(np.float64)
+    assert one.shape == (1, H, 350, 350)
+    np.testing.assert_allclose(one, two, rtol=2e-3, atol=2e-7)
+    np.testing.assert_allclose(one.sum(axis=-1), 1.0, rtol=0, atol=2e-4)
