@@ -59,23 +59,29 @@ def parse_args():
                     help="skip the MFMA-only probe (zero vs random operands) that gives the practical ceiling")
     ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
     ap.add_argument("--no-energy", action="store_true", help="skip the calibration kernels (block energy, spatial similarity)")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "2wg", "duo"],
+                    help="schedule of the forward (the `kernel` field of calibatt_fwd_options): the library's "
+                         "choice, the two-workgroup kernel, or the duo kernel")
     ap.add_argument("--anchor-k", type=int, nargs="*", default=None,
                     help="anchor rows per frame to time (default: the k of the paper's table)")
     return ap.parse_args()
 
 
-def time_launches(pkg, torch, q, k, v, out, dp, scale, steps, warmup):
+KERNELS = {"auto": 0, "2wg": 1, "duo": 2}
+
+
+def time_launches(pkg, torch, q, k, v, out, dp, scale, steps, warmup, kernel=0):
     """Returns (ms_per_step by wall clock, mean kernel ms by HIP events)."""
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
-        pkg.sparse_attn_fwd(q, k, v, out, dp, scale)
+        pkg.sparse_attn_fwd(q, k, v, out, dp, scale, kernel=kernel)
     torch.cuda.synchronize()
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     t0 = time.perf_counter()
     for i in range(steps):
         starts[i].record(stream)
-        pkg.sparse_attn_fwd(q, k, v, out, dp, scale)
+        pkg.sparse_attn_fwd(q, k, v, out, dp, scale, kernel=kernel)
         stops[i].record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
@@ -389,7 +395,8 @@ def main():
     tile_flops = 4.0 * wl.block_q * wl.block_k * wl.D
     flops = hp.nnz * wl.B * tile_flops
 
-    wall_ms, ev_mean_ms, ev_med_ms = time_launches(pkg, torch, q, k, v, out, dp, wl.scale, args.steps, args.warmup)
+    wall_ms, ev_mean_ms, ev_med_ms = time_launches(pkg, torch, q, k, v, out, dp, wl.scale, args.steps, args.warmup,
+                                                    KERNELS[args.kernel])
     value = flops / (wall_ms * 1e-3) / 1e12
     achieved = flops / (ev_mean_ms * 1e-3) / 1e12
 
@@ -404,7 +411,8 @@ def main():
     if not args.no_dense:
         wd = make_workload(args.workload, dense=True, with_qkv=False, heads=args.heads)
         hd = pkg.compile_pattern(wd.mask, wd.repeat, wd.H, wd.N, wd.block_q, wd.block_k, args.order).to_device(persistent=not args.no_persistent)
-        d_wall, d_ev, d_med = time_launches(pkg, torch, q, k, v, out, hd, wl.scale, max(3, args.steps // 4), 1)
+        d_wall, d_ev, d_med = time_launches(pkg, torch, q, k, v, out, hd, wl.scale, max(3, args.steps // 4), 1,
+                                            KERNELS[args.kernel])
         dense = {"ms": d_ev, "tflops": hd.nnz * wl.B * tile_flops / (d_ev * 1e-3) / 1e12,
                  "speedup_sparse_vs_dense": d_ev / ev_mean_ms}
 
@@ -448,7 +456,7 @@ def main():
         "kernel_ms_median": ev_med_ms,
         "dense_reference": dense,
         "observed_clock": observed,
-        "kernel_variant": os.environ.get("CALIBATT_KERNEL", "2wg"),
+        "kernel": args.kernel,
         "roofline": {
             "bound": "mfma",
             "achieved": achieved,

@@ -24,9 +24,13 @@
  * forward reads directly), calibatt_merge_intervals(),
  * calibatt_share_timesteps().
  *
- * Plain C, no exceptions cross the boundary, no global state is kept between
- * calls, every buffer is owned by the caller; the library allocates no device
- * memory (scratch comes in through workspace arguments).  All functions return a
+ * Plain C, no exceptions cross the boundary, every buffer is owned by the
+ * caller, and the library allocates no device memory (scratch comes in through
+ * workspace arguments).  Nothing in the environment changes what a call does.
+ * The only state kept between calls is a per-device cache of launch facts (how
+ * many workgroups of a kernel the device holds), filled on first use through
+ * atomics: calls may come from any number of host threads at once, as long as
+ * calls that overlap on the GPU use separate workspaces.  All functions return a
  * calibatt_status (0 = success, negative = error) unless stated otherwise.
  */
 #ifndef CALIBATT_H
@@ -231,16 +235,31 @@ int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, const void *v
  *           of exp(scale * q.k), -inf for a query that keeps no key; queries of
  *           a repeated block receive the value of their source row.  With it,
  *           results over disjoint key sets can be merged exactly.
+ *   kernel  which of the two schedules of the same tile loop (Section 2,
+ *           Eq. 3-4) runs.  CALIBATT_KERNEL_AUTO (0, what the other entry
+ *           points use): the duo schedule - one workgroup per CU whose two
+ *           halves alternate matrix and softmax phases - where it applies
+ *           (block_q = 128, a pattern with a work_counter, more work items
+ *           than the device runs at a time, interval rows of at most 2048
+ *           kept blocks), else the two-workgroups-per-CU schedule.
+ *           CALIBATT_KERNEL_TWO_WORKGROUPS forces the latter;
+ *           CALIBATT_KERNEL_DUO forces the former whatever the number of work
+ *           items and fails with UNSUPPORTED where its other conditions do
+ *           not hold.  Both meet the same tolerance; their
+ *           outputs differ in the last bits (the duo schedule moves the
+ *           reference of its exponentials lazily).
  * Everything else as in calibatt_sparse_attn_fwd.
  * Errors: as calibatt_sparse_attn_fwd_strided; NULL (options), UNSUPPORTED
- * (dtype), SHAPE (lse not 4-byte aligned).
+ * (dtype, kernel), SHAPE (lse not 4-byte aligned).
  */
 enum { CALIBATT_BF16 = 0, CALIBATT_F16 = 1 };
+enum { CALIBATT_KERNEL_AUTO = 0, CALIBATT_KERNEL_TWO_WORKGROUPS = 1, CALIBATT_KERNEL_DUO = 2 };
 typedef struct calibatt_fwd_options {
   const calibatt_strides *in_strides;
   const calibatt_strides *out_strides;
   int32_t dtype;
   float *lse;
+  int32_t kernel;
 } calibatt_fwd_options;
 int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const void *v, void *out, int B, int H,
                                 int N, int D, int block_q, int block_k,

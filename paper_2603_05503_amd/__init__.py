@@ -5,6 +5,9 @@ torch is used for device buffers and streams.  There is no fallback: if the
 library has not been built, loading fails with an error.
 """
 from .binding import (  # noqa: F401
+    KERNEL_AUTO,
+    KERNEL_DUO,
+    KERNEL_TWO_WORKGROUPS,
     CalibattError,
     DeviceAnchorMap,
     DevicePattern,

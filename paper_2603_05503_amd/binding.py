@@ -25,7 +25,10 @@ class _CStrides(C.Structure):
 
 class _CFwdOptions(C.Structure):
     _fields_ = [("in_strides", C.POINTER(_CStrides)), ("out_strides", C.POINTER(_CStrides)),
-                ("dtype", C.c_int32), ("lse", C.c_void_p)]
+                ("dtype", C.c_int32), ("lse", C.c_void_p), ("kernel", C.c_int32)]
+
+
+KERNEL_AUTO, KERNEL_TWO_WORKGROUPS, KERNEL_DUO = 0, 1, 2
 
 
 class _CPattern(C.Structure):
@@ -320,13 +323,15 @@ class DevicePattern:
 
 
 def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
-                    block_q: Optional[int] = None, block_k: Optional[int] = None, stream=None, lse=None):
+                    block_q: Optional[int] = None, block_k: Optional[int] = None, stream=None, lse=None,
+                    kernel: int = KERNEL_AUTO):
     """The sparse forward on torch CUDA tensors of logical shape [B, H, N, D], bf16 or fp16 (all four
     alike).  The tensors may be strided views (e.g. ``x.transpose(1, 2)`` of a [B, N, H, D] tensor, or
     slices of a fused [B, N, 3, H, D] projection) as long as D is contiguous and q, k, v share their
     strides.  ``lse``: optional contiguous fp32 CUDA tensor [B, H, N] that receives the log-sum-exp of
-    every query's kept logits.  Packed bf16 calls without ``lse`` go through calibatt_sparse_attn_fwd,
-    everything else through calibatt_sparse_attn_fwd_ex."""
+    every query's kept logits.  ``kernel``: KERNEL_AUTO, KERNEL_TWO_WORKGROUPS or KERNEL_DUO (the
+    ``kernel`` field of calibatt_fwd_options).  Packed bf16 calls without ``lse`` and with the automatic
+    kernel choice go through calibatt_sparse_attn_fwd, everything else through calibatt_sparse_attn_fwd_ex."""
     import torch
 
     lib = load_library()
@@ -346,14 +351,14 @@ def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
     packed = all(t.is_contiguous() for t in (q, k, v, out))
-    if packed and lse is None and q.dtype == torch.bfloat16:
+    if packed and lse is None and q.dtype == torch.bfloat16 and kernel == KERNEL_AUTO:
         st = lib.calibatt_sparse_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
                                           B, H, N, D, bq, bk, C.byref(pattern.c), float(scale), C.c_void_p(stream))
     else:
         si = _CStrides(q.stride(0), q.stride(1), q.stride(2))
         so = _CStrides(out.stride(0), out.stride(1), out.stride(2))
         opt = _CFwdOptions(None if packed else C.pointer(si), None if packed else C.pointer(so),
-                           0 if q.dtype == torch.bfloat16 else 1, None if lse is None else lse.data_ptr())
+                           0 if q.dtype == torch.bfloat16 else 1, None if lse is None else lse.data_ptr(), int(kernel))
         st = lib.calibatt_sparse_attn_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
                                              B, H, N, D, bq, bk, C.byref(pattern.c), float(scale),
                                              C.byref(opt), C.c_void_p(stream))

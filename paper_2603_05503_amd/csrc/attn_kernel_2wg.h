@@ -65,9 +65,10 @@ struct RowBlock {
   float m_run;  // running max of scaled (log2-domain) logits, shared by lane and lane^32
   float l_run;  // this lane's share of the running row sum
 
-  __device__ __forceinline__ explicit RowBlock(char *lds_, uint32_t kv_row_bytes_ = ROWB)
+  // tid_: index of the thread among the NT threads that share this row block
+  __device__ __forceinline__ explicit RowBlock(char *lds_, uint32_t kv_row_bytes_ = ROWB, int tid_ = threadIdx.x)
       : lds(lds_), ldsK(lds_), ldsV(lds_ + TILE_BYTES), kv_row_bytes(kv_row_bytes_) {
-    tid = threadIdx.x;
+    tid = tid_;
     lane = tid & 63;
     wave = tid >> 6;
     l32 = lane & 31;

@@ -4,16 +4,14 @@
 #include <stdint.h>
 
 #include <algorithm>
-#include <cstdlib>
-#include <cstring>
+#include <atomic>
 
 #include "attn_kernel_2wg.h"
 #include "attn_kernel_anchor.h"
 #include "attn_kernel_energy.h"
 #include "attn_kernel_similarity.h"
 #include "calibration_kernels.h"
-#include "attn_kernel_pipe.h"
-#include "attn_kernel_pp.h"
+#include "attn_kernel_duo.h"
 #include "calibatt.h"
 
 namespace {
@@ -31,27 +29,41 @@ struct FwdPtrs {
   int dtype;                // CALIBATT_BF16 or CALIBATT_F16
 };
 
-// Per-device launch facts, looked up once per kernel and device.
+// Per-device launch facts of one kernel: how many workgroups the whole device holds at a time.
+// Looked up on the first call per device.  Concurrent first calls all compute the same figure, so
+// the slot is a plain atomic (0 = not known yet) and no lock is taken.
 struct DevInfo {
-  bool ready = false;
-  int slots = 0;  // co-resident workgroups on the whole device
+  std::atomic<int> slots[64];
 };
 
 template <typename Kernel>
-int prepare(Kernel kernel, int threads, int smem, DevInfo (&info)[64], int &slots) {
+int prepare(Kernel kernel, int threads, int smem, DevInfo &info, int &slots) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CALIBATT_ERR_LAUNCH;
-  if (!info[dev].ready) {
-    int cus = 0, per_cu = 0;
-    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kernel, threads, smem) != hipSuccess ||
-        cus <= 0 || per_cu <= 0)
-      return CALIBATT_ERR_LAUNCH;
-    info[dev].slots = cus * per_cu;
-    info[dev].ready = true;
-  }
-  slots = info[dev].slots;
+  slots = info.slots[dev].load(std::memory_order_acquire);
+  if (slots > 0) return CALIBATT_OK;
+  int cus = 0, per_cu = 0;
+  if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kernel, threads, smem) != hipSuccess ||
+      cus <= 0 || per_cu <= 0)
+    return CALIBATT_ERR_LAUNCH;
+  slots = cus * per_cu;
+  info.slots[dev].store(slots, std::memory_order_release);
+  return CALIBATT_OK;
+}
+
+// Registers a kernel's dynamic LDS ceiling once per device (same scheme as above).
+struct DevReady {
+  std::atomic<int> ready[64];
+};
+template <typename Kernel>
+int register_lds(Kernel kernel, int smem, DevReady &state, int &dev) {
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CALIBATT_ERR_LAUNCH;
+  if (state.ready[dev].load(std::memory_order_acquire)) return CALIBATT_OK;
+  if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+    return CALIBATT_ERR_LAUNCH;
+  state.ready[dev].store(1, std::memory_order_release);
   return CALIBATT_OK;
 }
 
@@ -65,85 +77,57 @@ int launch_kernel(Kernel kernel, unsigned grid, int threads, int smem, hipStream
              : CALIBATT_ERR_LAUNCH;
 }
 
-// TAKES_IV: the kernel has the two trailing interval-list parameters (the two-workgroup kernel).
-template <bool TAKES_IV, typename Kernel>
+// Grid of the two-workgroup kernel: persistent workgroups popping from the counters when there are
+// more items than the device holds workgroups, one workgroup per item otherwise.
+template <typename Kernel>
 int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, const FwdDims &p, hipStream_t stream) {
   const long long items = (long long)p.n_work * p.B;
   long long grid = items;
   int32_t *counter = a.counter;
   if (counter && items > slots) grid = slots; else counter = nullptr;
-  if constexpr (TAKES_IV)
-    return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
-                         a.work, a.fan_ptr, a.fan_dst, counter, p, a.iv_ptr, a.iv, a.head_map, a.lse);
-  else
-    return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
-                         a.work, a.fan_ptr, a.fan_dst, counter, p);
+  return launch_kernel(kernel, (unsigned)grid, threads, smem, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
+                       a.work, a.fan_ptr, a.fan_dst, counter, p, a.iv_ptr, a.iv, a.head_map, a.lse);
 }
 
-// CALIBATT_KERNEL in the environment selects the kernel where its shape is covered: "pp" the
-// ping-pong kernel (two wavefront groups per workgroup), "pipe" the in-wave pipelined one,
-// anything else the two-workgroups-per-CU kernel.  All compute the same thing.  Read per call.
-enum class Variant { TwoWg, Pipe, PingPong };
-Variant wanted_variant() {
-  const char *e = std::getenv("CALIBATT_KERNEL");
-  if (e && std::strcmp(e, "pipe") == 0) return Variant::Pipe;
-  if (e && std::strcmp(e, "pp") == 0) return Variant::PingPong;
-  return Variant::TwoWg;
+// IV: the pattern comes as intervals.  The duo kernel (attn_kernel_duo.h) serves 128-row query
+// blocks when the launch is persistent and has more items than the device has half-workgroups;
+// everything else runs the two-workgroup kernel (attn_kernel_2wg.h).  `which`: CALIBATT_KERNEL_*.
+template <int D, int BQ, int BK, bool IV, typename T>
+int launch_typed(const FwdPtrs &a, const FwdDims &p, int max_row, int which, hipStream_t stream) {
+  const long long items = (long long)p.n_work * p.B;
+  int slots = 0;
+  if constexpr (BQ == 128) {
+    if (which != CALIBATT_KERNEL_TWO_WORKGROUPS && a.counter && (!IV || max_row <= IV_COLS)) {
+      static DevInfo info;
+      using Row = DuoRow<D, BQ, BK, T>;
+      constexpr int SMEM = 2 * Row::LDS_BYTES + 64 + (IV ? 2 * IV_COLS * 4 : 0);
+      auto kernel = sparse_attn_fwd_duo_kernel<D, BQ, BK, IV, T>;
+      if (int st = prepare(kernel, BQ * 4, SMEM, info, slots)) return st;
+      if (items > 2LL * slots || which == CALIBATT_KERNEL_DUO) {
+        const long long grid = std::min<long long>(slots, (items + 1) / 2);
+        return launch_kernel(kernel, (unsigned)grid, BQ * 4, SMEM, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
+                             a.work, a.fan_ptr, a.fan_dst, a.counter, p, a.iv_ptr, a.iv, a.head_map, a.lse);
+      }
+    }
+  }
+  if (which == CALIBATT_KERNEL_DUO) return CALIBATT_ERR_UNSUPPORTED;
+  static DevInfo info;
+  constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + (IV ? IV_COLS * 4 : 0);
+  auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, IV, T>;
+  if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
+  return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
 }
 
 template <int D, int BQ, int BK>
-int launch(const FwdPtrs &a, const FwdDims &p, int max_row, hipStream_t stream) {
+int launch(const FwdPtrs &a, const FwdDims &p, int max_row, int which, hipStream_t stream) {
   const long long items = (long long)p.n_work * p.B;
   if (items <= 0) return CALIBATT_OK;
   if (items > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
-  int slots = 0;
-  if (a.dtype == CALIBATT_F16) {  // fp16 tensors: the two-workgroup kernel only
-    static DevInfo info[2][64];
-    if (a.iv) {
-      constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + IV_COLS * 4;
-      auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, true, F16>;
-      if (int st = prepare(kernel, BQ * 2, SMEM, info[1], slots)) return st;
-      return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
-    }
-    constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64;
-    auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, false, F16>;
-    if (int st = prepare(kernel, BQ * 2, SMEM, info[0], slots)) return st;
-    return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
-  }
-  if (a.iv) {  // interval-encoded pattern: read by the two-workgroup kernel only
-    static DevInfo info[64];
-    constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + IV_COLS * 4;
-    auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, true>;
-    if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
-    return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
-  }
-  // the alternative kernels read packed [B][H][N][D] tensors only
-  const bool packed = p.in.n == D && p.in.h == (long long)p.N * D && p.in.b == (long long)p.H * p.N * D &&
-                      p.out.n == D && p.out.h == (long long)p.N * D && p.out.b == (long long)p.H * p.N * D;
-  const Variant variant = packed && !a.head_map && !a.lse ? wanted_variant() : Variant::TwoWg;
-  if constexpr (BQ <= BK) {
-    if (variant == Variant::PingPong) {
-      static DevInfo info[64];
-      constexpr int SMEM = PpLds<D, BQ, BK>::BYTES;
-      auto kernel = sparse_attn_fwd_pp_kernel<D, BQ, BK>;
-      if (int st = prepare(kernel, BQ * 4, SMEM, info, slots)) return st;
-      return enqueue<false>(kernel, BQ * 4, SMEM, slots, a, p, stream);
-    }
-  }
-  if constexpr (D == 128 && BQ == 128 && BK == 128) {
-    if (max_row <= PIPE_COL_CAP && variant == Variant::Pipe) {
-      static DevInfo info[64];
-      constexpr int SMEM = PipeLds<D, BQ, BK>::BYTES;
-      auto kernel = sparse_attn_fwd_pipe_kernel<D, BQ, BK>;
-      if (int st = prepare(kernel, PIPE_THREADS, SMEM, info, slots)) return st;
-      return enqueue<false>(kernel, PIPE_THREADS, SMEM, slots, a, p, stream);
-    }
-  }
-  constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64;
-  static DevInfo info[64];
-  auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, false>;
-  if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
-  return enqueue<true>(kernel, BQ * 2, SMEM, slots, a, p, stream);
+  if (a.dtype == CALIBATT_F16)
+    return a.iv ? launch_typed<D, BQ, BK, true, F16>(a, p, max_row, which, stream)
+                : launch_typed<D, BQ, BK, false, F16>(a, p, max_row, which, stream);
+  return a.iv ? launch_typed<D, BQ, BK, true, Bf16>(a, p, max_row, which, stream)
+              : launch_typed<D, BQ, BK, false, Bf16>(a, p, max_row, which, stream);
 }
 
 bool strides_ok(const calibatt_strides &t, int B, int H, int N, int D) {
@@ -191,7 +175,7 @@ long long anchor_workspace_bytes(const AnchorDims &p) {
 // slots of one XCD for the anchor kernel on the current device
 template <int D>
 int anchor_slots(int &slots_per_xcd) {
-  static DevInfo info[64];
+  static DevInfo info;
   int slots = 0;
   if (int st = prepare(anchor_attn_fwd_kernel<D>, ANCHOR_BQ * 2, AnchorLds<D>::BYTES, info, slots)) return st;
   slots_per_xcd = slots / ANCHOR_XCDS;
@@ -226,7 +210,7 @@ int launch_anchor(const FwdPtrs &a, const int32_t *head_ids, const int32_t *q_in
                              a.k, a.v, a.out, head_ids, q_index, dst_ptr, dst_idx, workspace, p))
     return st;
   if (p.n_split == 1) return CALIBATT_OK;
-  static DevInfo merge_info[64];
+  static DevInfo merge_info;
   int unused = 0;
   if (int st = prepare(anchor_merge_kernel<D>, ANCHOR_BQ * 2, AnchorLds<D>::MERGE_BYTES, merge_info, unused)) return st;
   return launch_kernel(anchor_merge_kernel<D>, (unsigned)(ANCHOR_XCDS * p.rem_max), ANCHOR_BQ * 2,
@@ -245,15 +229,9 @@ int launch_energy(const uint16_t *q, const uint16_t *k, float *energy, const Ene
   const long long smem = EnergyLds<D, BQ, BK>::bytes(p.nbk);
   if (smem > ENERGY_MAX_LDS) return CALIBATT_ERR_UNSUPPORTED;
   auto kernel = block_energy_kernel<D, BQ, BK>;
-  static bool ready[64];
+  static DevReady state;
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CALIBATT_ERR_LAUNCH;
-  if (!ready[dev]) {
-    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ENERGY_MAX_LDS) !=
-        hipSuccess)
-      return CALIBATT_ERR_LAUNCH;
-    ready[dev] = true;
-  }
+  if (int st = register_lds(kernel, ENERGY_MAX_LDS, state, dev)) return st;
   return launch_kernel(kernel, (unsigned)grid, BQ * 2, (int)smem, stream, q, k, energy, p);
 }
 
@@ -268,15 +246,9 @@ int launch_energy_onepass(const uint16_t *q, const uint16_t *k, float *energy, c
   const long long slice = (long long)p.nbk * BQ * 4;
   if (workspace_bytes < slice) return CALIBATT_ERR_BUFFER_TOO_SMALL;
   auto kernel = block_energy_onepass_kernel<D, BQ, BK>;
-  static bool ready[64];
+  static DevReady state;
   int dev = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CALIBATT_ERR_LAUNCH;
-  if (!ready[dev]) {
-    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ENERGY_MAX_LDS) !=
-        hipSuccess)
-      return CALIBATT_ERR_LAUNCH;
-    ready[dev] = true;
-  }
+  if (int st = register_lds(kernel, ENERGY_MAX_LDS, state, dev)) return st;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
       hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kernel, BQ * 2, (size_t)smem) != hipSuccess ||
       cus <= 0 || per_cu <= 0)
@@ -296,7 +268,7 @@ int launch_similarity(const uint16_t *q, const uint16_t *k, const int32_t *partn
   if (grid > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
   constexpr int SMEM = 2 * RowBlock<D, SIM_BQ, SIM_BK>::TILE_BYTES;
   auto kernel = pair_similarity_kernel<D>;
-  static DevInfo info[64];
+  static DevInfo info;
   int slots = 0;
   if (int st = prepare(kernel, SIM_BQ * 2, SMEM, info, slots)) return st;
   if (int st = launch_kernel(kernel, (unsigned)grid, SIM_BQ * 2, SMEM, stream, q, k, partner, triples, p)) return st;
@@ -529,6 +501,7 @@ extern "C" int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, co
   opt.out_strides = out_strides;
   opt.dtype = CALIBATT_BF16;
   opt.lse = nullptr;
+  opt.kernel = CALIBATT_KERNEL_AUTO;
   return calibatt_sparse_attn_fwd_ex(q, k, v, out, B, H, N, D, block_q, block_k, pattern, scale, &opt, stream);
 }
 
@@ -538,6 +511,9 @@ extern "C" int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const v
                                            const calibatt_fwd_options *options, void *stream) {
   if (!options) return CALIBATT_ERR_NULL;
   if (options->dtype != CALIBATT_BF16 && options->dtype != CALIBATT_F16) return CALIBATT_ERR_UNSUPPORTED;
+  if (options->kernel != CALIBATT_KERNEL_AUTO && options->kernel != CALIBATT_KERNEL_TWO_WORKGROUPS &&
+      options->kernel != CALIBATT_KERNEL_DUO)
+    return CALIBATT_ERR_UNSUPPORTED;
   if (B <= 0 || H <= 0 || N <= 0 || D <= 0) return q && k && v && out && pattern ? CALIBATT_ERR_SHAPE : CALIBATT_ERR_NULL;
   const calibatt_strides packed_strides = {(int64_t)H * N * D, (int64_t)N * D, (int64_t)D};
   const calibatt_strides *in_strides = options->in_strides ? options->in_strides : &packed_strides;
@@ -597,7 +573,7 @@ extern "C" int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const v
   p.out = Strides{out_strides->b, out_strides->h, out_strides->n};
   hipStream_t s = (hipStream_t)stream;
 #define CALIBATT_CASE(d, bq, bk) \
-  if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, pattern->max_row, s);
+  if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, pattern->max_row, options->kernel, s);
   CALIBATT_CASE(128, 128, 128)
   CALIBATT_CASE(128, 128, 64)
   CALIBATT_CASE(128, 64, 128)

@@ -20,11 +20,29 @@ def lib():
     return pkg
 
 
-@pytest.fixture(params=["2wg", "pipe", "pp"])
+@pytest.fixture(params=["auto", "2wg", "duo"])
 def kernel_variant(request, monkeypatch):
-    """Runs a GPU test once per kernel: the library reads CALIBATT_KERNEL on every call.  "pipe"
-    selects the in-wave pipelined kernel for 128 x 128 x 128 blocks, "pp" the ping-pong kernel for
-    shapes with block_q <= block_k; shapes a variant does not cover take the default
-    two-workgroup kernel."""
-    monkeypatch.setenv("CALIBATT_KERNEL", request.param)
+    """Runs a GPU test once per schedule of the forward: the library's own choice, the
+    two-workgroup kernel forced, and the duo kernel forced wherever it applies (shapes it does not
+    cover - block_q = 64, patterns without a work counter - take the library's choice)."""
+    import paper_2603_05503_amd as pkg
+    from paper_2603_05503_amd import binding
+
+    if request.param == "auto":
+        return request.param
+    plain = binding.sparse_attn_fwd
+    forced = binding.KERNEL_TWO_WORKGROUPS if request.param == "2wg" else binding.KERNEL_DUO
+
+    def variant(q, k, v, out, pattern, scale, *args, **kwargs):
+        if "kernel" in kwargs:
+            return plain(q, k, v, out, pattern, scale, *args, **kwargs)
+        try:
+            return plain(q, k, v, out, pattern, scale, *args, kernel=forced, **kwargs)
+        except binding.CalibattError as e:
+            if e.status != -3:  # CALIBATT_ERR_UNSUPPORTED: the forced kernel does not cover this call
+                raise
+            return plain(q, k, v, out, pattern, scale, *args, **kwargs)
+
+    monkeypatch.setattr(pkg, "sparse_attn_fwd", variant)
+    monkeypatch.setattr(binding, "sparse_attn_fwd", variant)
     return request.param
