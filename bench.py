@@ -59,15 +59,15 @@ def parse_args():
                     help="skip the MFMA-only probe (zero vs random operands) that gives the practical ceiling")
     ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
     ap.add_argument("--no-energy", action="store_true", help="skip the calibration kernels (block energy, spatial similarity)")
-    ap.add_argument("--kernel", default="auto", choices=["auto", "2wg", "duo"],
+    ap.add_argument("--kernel", default="auto", choices=["auto", "2wg", "il"],
                     help="schedule of the forward (the `kernel` field of calibatt_fwd_options): the library's "
-                         "choice, the two-workgroup kernel, or the duo kernel")
+                         "choice, the two-workgroup kernel, or the interleaved kernel")
     ap.add_argument("--anchor-k", type=int, nargs="*", default=None,
                     help="anchor rows per frame to time (default: the k of the paper's table)")
     return ap.parse_args()
 
 
-KERNELS = {"auto": 0, "2wg": 1, "duo": 2}
+KERNELS = {"auto": 0, "2wg": 1, "il": 2}
 
 
 def time_launches(pkg, torch, q, k, v, out, dp, scale, steps, warmup, kernel=0):

@@ -237,23 +237,23 @@ int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, const void *v
  *           results over disjoint key sets can be merged exactly.
  *   kernel  which of the two schedules of the same tile loop (Section 2,
  *           Eq. 3-4) runs.  CALIBATT_KERNEL_AUTO (0, what the other entry
- *           points use): the duo schedule - one workgroup per CU whose two
- *           halves alternate matrix and softmax phases - where it applies
- *           (block_q = 128, a pattern with a work_counter, more work items
- *           than the device runs at a time, interval rows of at most 2048
- *           kept blocks), else the two-workgroups-per-CU schedule.
- *           CALIBATT_KERNEL_TWO_WORKGROUPS forces the latter;
- *           CALIBATT_KERNEL_DUO forces the former whatever the number of work
- *           items and fails with UNSUPPORTED where its other conditions do
- *           not hold.  Both meet the same tolerance; their
- *           outputs differ in the last bits (the duo schedule moves the
- *           reference of its exponentials lazily).
+ *           points use): the interleaved schedule - every wavefront issues
+ *           the MFMAs of two contractions and the softmax of a third
+ *           sub-tile as one instruction stream - wherever it applies
+ *           (interval rows of at most 2048 kept blocks), else the
+ *           two-workgroup schedule, which runs the three phases of a tile
+ *           one after the other.  CALIBATT_KERNEL_TWO_WORKGROUPS forces the
+ *           latter; CALIBATT_KERNEL_INTERLEAVED forces the former and fails
+ *           with UNSUPPORTED where it does not apply.  Both meet the same
+ *           tolerance; their outputs differ in the last bits (the
+ *           interleaved schedule moves the reference of its exponentials
+ *           lazily).
  * Everything else as in calibatt_sparse_attn_fwd.
  * Errors: as calibatt_sparse_attn_fwd_strided; NULL (options), UNSUPPORTED
  * (dtype, kernel), SHAPE (lse not 4-byte aligned).
  */
 enum { CALIBATT_BF16 = 0, CALIBATT_F16 = 1 };
-enum { CALIBATT_KERNEL_AUTO = 0, CALIBATT_KERNEL_TWO_WORKGROUPS = 1, CALIBATT_KERNEL_DUO = 2 };
+enum { CALIBATT_KERNEL_AUTO = 0, CALIBATT_KERNEL_TWO_WORKGROUPS = 1, CALIBATT_KERNEL_INTERLEAVED = 2 };
 typedef struct calibatt_fwd_options {
   const calibatt_strides *in_strides;
   const calibatt_strides *out_strides;

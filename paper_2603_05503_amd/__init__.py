@@ -6,7 +6,7 @@ library has not been built, loading fails with an error.
 """
 from .binding import (  # noqa: F401
     KERNEL_AUTO,
-    KERNEL_DUO,
+    KERNEL_INTERLEAVED,
     KERNEL_TWO_WORKGROUPS,
     CalibattError,
     DeviceAnchorMap,

@@ -28,7 +28,7 @@ class _CFwdOptions(C.Structure):
                 ("dtype", C.c_int32), ("lse", C.c_void_p), ("kernel", C.c_int32)]
 
 
-KERNEL_AUTO, KERNEL_TWO_WORKGROUPS, KERNEL_DUO = 0, 1, 2
+KERNEL_AUTO, KERNEL_TWO_WORKGROUPS, KERNEL_INTERLEAVED = 0, 1, 2
 
 
 class _CPattern(C.Structure):
@@ -329,7 +329,7 @@ def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
     alike).  The tensors may be strided views (e.g. ``x.transpose(1, 2)`` of a [B, N, H, D] tensor, or
     slices of a fused [B, N, 3, H, D] projection) as long as D is contiguous and q, k, v share their
     strides.  ``lse``: optional contiguous fp32 CUDA tensor [B, H, N] that receives the log-sum-exp of
-    every query's kept logits.  ``kernel``: KERNEL_AUTO, KERNEL_TWO_WORKGROUPS or KERNEL_DUO (the
+    every query's kept logits.  ``kernel``: KERNEL_AUTO, KERNEL_TWO_WORKGROUPS or KERNEL_INTERLEAVED (the
     ``kernel`` field of calibatt_fwd_options).  Packed bf16 calls without ``lse`` and with the automatic
     kernel choice go through calibatt_sparse_attn_fwd, everything else through calibatt_sparse_attn_fwd_ex."""
     import torch

@@ -34,11 +34,26 @@ def hipcc() -> str:
 
 
 def build(verbose: bool = True, extra_flags=()) -> str:
+    import importlib.util
+    import tempfile
+
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [hipcc(), *HIP_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, *srcs, "-o", LIB_PATH]
+    # --save-temps leaves the device assembly of this very compilation in the working directory:
+    # the kernels that name registers by hand are checked on it (csrc/check_named_regs.py).
+    cmd = [hipcc(), *HIP_FLAGS, *extra_flags, "--save-temps", "-I", os.path.join(ROOT, "include"), "-I", CSRC, *srcs,
+           "-o", LIB_PATH]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    with tempfile.TemporaryDirectory() as tmp:
+        subprocess.run(cmd, check=True, cwd=tmp)
+        spec = importlib.util.spec_from_file_location("check_named_regs", os.path.join(CSRC, "check_named_regs.py"))
+        mod = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(mod)
+        asm = os.path.join(tmp, "sparse_attn_fwd-hip-amdgcn-amd-amdhsa-gfx950.s")
+        problems = mod.check(open(asm).read())
+    if problems:
+        os.remove(LIB_PATH)
+        raise RuntimeError("named-register kernels: the compiler used a reserved register:\n" + "\n".join(problems[:20]))
     probe = [hipcc(), *[f for f in HIP_FLAGS if f not in ("-fPIC", "-shared")], "-Wno-unused-value",
              os.path.join(CSRC, "mfma_peak_probe.hip"), "-o", PROBE_PATH]
     if verbose:

@@ -108,15 +108,18 @@ struct TileLoader {
     return (tid / CH) * row_bytes + c * 16;
   }
 
+  // Instruction `it` of the ITERS that fill the tile.
   // lds_wave_off: LDS byte address of the tile + 1024 * wave index (wave-uniform)
+  static __device__ __forceinline__ void issue_one(int it, const u32x4 rsrc, int row0, uint32_t lds_wave_off, int tid,
+                                                   uint32_t lane_off0, uint32_t row_bytes = D * 2) {
+    const uint32_t voff = INVARIANT ? lane_off0 : lane_offset(tid, it, row_bytes);
+    const uint32_t soff = (uint32_t)(row0 + it * RPI) * row_bytes;
+    dma_16B_per_lane(rsrc, voff, soff, lds_wave_off + it * NT * 16);
+  }
   static __device__ __forceinline__ void issue(const u32x4 rsrc, int row0, uint32_t lds_wave_off, int tid,
                                                uint32_t lane_off0, uint32_t row_bytes = D * 2) {
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-      const uint32_t voff = INVARIANT ? lane_off0 : lane_offset(tid, it, row_bytes);
-      const uint32_t soff = (uint32_t)(row0 + it * RPI) * row_bytes;
-      dma_16B_per_lane(rsrc, voff, soff, lds_wave_off + it * NT * 16);
-    }
+    for (int it = 0; it < ITERS; ++it) issue_one(it, rsrc, row0, lds_wave_off, tid, lane_off0, row_bytes);
   }
 };
 

@@ -11,7 +11,7 @@
 #include "attn_kernel_energy.h"
 #include "attn_kernel_similarity.h"
 #include "calibration_kernels.h"
-#include "attn_kernel_duo.h"
+#include "attn_kernel_il.h"
 #include "calibatt.h"
 
 namespace {
@@ -89,28 +89,21 @@ int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, c
                        a.work, a.fan_ptr, a.fan_dst, counter, p, a.iv_ptr, a.iv, a.head_map, a.lse);
 }
 
-// IV: the pattern comes as intervals.  The duo kernel (attn_kernel_duo.h) serves 128-row query
-// blocks when the launch is persistent and has more items than the device has half-workgroups;
-// everything else runs the two-workgroup kernel (attn_kernel_2wg.h).  `which`: CALIBATT_KERNEL_*.
+// IV: the pattern comes as intervals.  `which` (CALIBATT_KERNEL_*) picks the schedule of the tile
+// loop: the interleaved kernel (attn_kernel_il.h) or the two-workgroup kernel (attn_kernel_2wg.h).
+// Interval rows longer than the interleaved kernel's column list take the two-workgroup kernel.
 template <int D, int BQ, int BK, bool IV, typename T>
 int launch_typed(const FwdPtrs &a, const FwdDims &p, int max_row, int which, hipStream_t stream) {
-  const long long items = (long long)p.n_work * p.B;
   int slots = 0;
-  if constexpr (BQ == 128) {
-    if (which != CALIBATT_KERNEL_TWO_WORKGROUPS && a.counter && (!IV || max_row <= IV_COLS)) {
-      static DevInfo info;
-      using Row = DuoRow<D, BQ, BK, T>;
-      constexpr int SMEM = 2 * Row::LDS_BYTES + 64 + (IV ? 2 * IV_COLS * 4 : 0);
-      auto kernel = sparse_attn_fwd_duo_kernel<D, BQ, BK, IV, T>;
-      if (int st = prepare(kernel, BQ * 4, SMEM, info, slots)) return st;
-      if (items > 2LL * slots || which == CALIBATT_KERNEL_DUO) {
-        const long long grid = std::min<long long>(slots, (items + 1) / 2);
-        return launch_kernel(kernel, (unsigned)grid, BQ * 4, SMEM, stream, a.q, a.k, a.v, a.out, a.row_ptr, a.col_idx,
-                             a.work, a.fan_ptr, a.fan_dst, a.counter, p, a.iv_ptr, a.iv, a.head_map, a.lse);
-      }
-    }
+  const bool il_fits = !IV || max_row <= IV_COLS;
+  if (which == CALIBATT_KERNEL_INTERLEAVED && !il_fits) return CALIBATT_ERR_UNSUPPORTED;
+  if (which == CALIBATT_KERNEL_INTERLEAVED || (which == CALIBATT_KERNEL_AUTO && il_fits)) {
+    static DevInfo info;
+    constexpr int SMEM = IlRow<D, BQ, BK, T>::LDS_BYTES + 64 + (IV ? IV_COLS * 4 : 0);
+    auto kernel = sparse_attn_fwd_il_kernel<D, BQ, BK, IV, T>;
+    if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
+    return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
   }
-  if (which == CALIBATT_KERNEL_DUO) return CALIBATT_ERR_UNSUPPORTED;
   static DevInfo info;
   constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + (IV ? IV_COLS * 4 : 0);
   auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, IV, T>;
@@ -512,7 +505,7 @@ extern "C" int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const v
   if (!options) return CALIBATT_ERR_NULL;
   if (options->dtype != CALIBATT_BF16 && options->dtype != CALIBATT_F16) return CALIBATT_ERR_UNSUPPORTED;
   if (options->kernel != CALIBATT_KERNEL_AUTO && options->kernel != CALIBATT_KERNEL_TWO_WORKGROUPS &&
-      options->kernel != CALIBATT_KERNEL_DUO)
+      options->kernel != CALIBATT_KERNEL_INTERLEAVED)
     return CALIBATT_ERR_UNSUPPORTED;
   if (B <= 0 || H <= 0 || N <= 0 || D <= 0) return q && k && v && out && pattern ? CALIBATT_ERR_SHAPE : CALIBATT_ERR_NULL;
   const calibatt_strides packed_strides = {(int64_t)H * N * D, (int64_t)N * D, (int64_t)D};
