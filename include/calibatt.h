@@ -237,15 +237,13 @@ int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, const void *v
  *           results over disjoint key sets can be merged exactly.
  *   kernel  which of the two schedules of the same tile loop (Section 2,
  *           Eq. 3-4) runs.  CALIBATT_KERNEL_AUTO (0, what the other entry
- *           points use): the interleaved schedule - every wavefront issues
- *           the MFMAs of two contractions and the softmax of a third
- *           sub-tile as one instruction stream - wherever it applies
- *           (interval rows of at most 2048 kept blocks), else the
- *           two-workgroup schedule, which runs the three phases of a tile
- *           one after the other.  CALIBATT_KERNEL_TWO_WORKGROUPS forces the
- *           latter; CALIBATT_KERNEL_INTERLEAVED forces the former and fails
- *           with UNSUPPORTED where it does not apply.  Both meet the same
- *           tolerance; their outputs differ in the last bits (the
+ *           points use) and CALIBATT_KERNEL_INTERLEAVED: every wavefront
+ *           issues the MFMAs of two contractions and the softmax of a third
+ *           sub-tile as one instruction stream.
+ *           CALIBATT_KERNEL_TWO_WORKGROUPS: the three phases of a tile run
+ *           one after the other, two workgroups per CU overlap as they
+ *           happen to fall; kept as the reference schedule.  Both meet the
+ *           same tolerance; their outputs differ in the last bits (the
  *           interleaved schedule moves the reference of its exponentials
  *           lazily).
  * Everything else as in calibatt_sparse_attn_fwd.

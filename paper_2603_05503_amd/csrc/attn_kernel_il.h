@@ -366,18 +366,24 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) __attribute__((amdgpu_
 
     const int cbeg = row_ptr[id];
     int n_tiles = row_ptr[id + 1] - cbeg;
-    if constexpr (IV) {
-      // the row's runs of consecutive key blocks expanded into the column list (rows of at most IV_COLS kept blocks)
-      const int ib = iv_ptr[id], ie = iv_ptr[id + 1] - 1;
-      n_tiles = (int)(iv[ie] >> 16);
+    // IV: entries [chunk_lo, chunk_lo + IV_COLS) of the row's list are expanded from its runs of
+    // consecutive key blocks into LDS; every thread takes runs tid, tid + NT, ...
+    int chunk_lo = 0;
+    auto expand_runs = [&]() {
+      const int ib = iv_ptr[id], ie = iv_ptr[id + 1] - 1;  // the last word only terminates the row
       for (int i = ib + tid; i < ie; i += NT) {
         const uint32_t w = iv[i], w_next = iv[i + 1];
         const int start = (int)(w & 0xffffu), before = (int)(w >> 16), len = (int)(w_next >> 16) - before;
-        for (int j = 0; j < len; ++j) cols[before + j] = start + j;
+        const int j0 = max(0, chunk_lo - before), j1 = min(len, chunk_lo + IV_COLS - before);
+        for (int j = j0; j < j1; ++j) cols[before + j - chunk_lo] = start + j;
       }
       __syncthreads();
+    };
+    if constexpr (IV) {
+      n_tiles = (int)(iv[iv_ptr[id + 1] - 1] >> 16);
+      expand_runs();  // the previous item's readers are behind the barrier that ended it
     }
-    auto col_at = [&](int entry) { return IV ? cols[entry] : col_idx[cbeg + entry]; };
+    auto col_at = [&](int entry) { return IV ? cols[entry - chunk_lo] : col_idx[cbeg + entry]; };
     // kept key blocks of the row, 64 at a time in one VGPR (lane j = entry j of the current 64)
     int col_cache = n_tiles > 0 ? col_at(min(lane, n_tiles - 1)) : 0;
     auto col_of = [&](int t) {  // t inside the cached 64
@@ -417,7 +423,15 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) __attribute__((amdgpu_
       for (int t = 1; t < n_tiles; ++t) {
         // stages 2t and 2t+1: block c = entry t of the list, c_prev = entry t-1, c_nx = entry t+1
         const int c = c1;
-        if (((t + 1) & 63) == 0 && t + 1 < n_tiles) col_cache = col_at(min(t + 1 + lane, n_tiles - 1));
+        if (((t + 1) & 63) == 0 && t + 1 < n_tiles) {
+          if constexpr (IV) {
+            if ((t + 1) % IV_COLS == 0) {  // every wave has taken its entries of the chunk that is replaced
+              chunk_lo = t + 1;
+              expand_runs();
+            }
+          }
+          col_cache = col_at(min(t + 1 + lane, n_tiles - 1));
+        }
         const int c_nx = t + 1 < n_tiles ? col_of(t + 1) : c;
         // loads inside the stream: V of u_(2t-1), K of u_(2t+1)
         IL_PROF(3);

@@ -91,13 +91,10 @@ int enqueue(Kernel kernel, int threads, int smem, int slots, const FwdPtrs &a, c
 
 // IV: the pattern comes as intervals.  `which` (CALIBATT_KERNEL_*) picks the schedule of the tile
 // loop: the interleaved kernel (attn_kernel_il.h) or the two-workgroup kernel (attn_kernel_2wg.h).
-// Interval rows longer than the interleaved kernel's column list take the two-workgroup kernel.
 template <int D, int BQ, int BK, bool IV, typename T>
-int launch_typed(const FwdPtrs &a, const FwdDims &p, int max_row, int which, hipStream_t stream) {
+int launch_typed(const FwdPtrs &a, const FwdDims &p, int which, hipStream_t stream) {
   int slots = 0;
-  const bool il_fits = !IV || max_row <= IV_COLS;
-  if (which == CALIBATT_KERNEL_INTERLEAVED && !il_fits) return CALIBATT_ERR_UNSUPPORTED;
-  if (which == CALIBATT_KERNEL_INTERLEAVED || (which == CALIBATT_KERNEL_AUTO && il_fits)) {
+  if (which != CALIBATT_KERNEL_TWO_WORKGROUPS) {
     static DevInfo info;
     constexpr int SMEM = IlRow<D, BQ, BK, T>::LDS_BYTES + 64 + (IV ? IV_COLS * 4 : 0);
     auto kernel = sparse_attn_fwd_il_kernel<D, BQ, BK, IV, T>;
@@ -112,15 +109,15 @@ int launch_typed(const FwdPtrs &a, const FwdDims &p, int max_row, int which, hip
 }
 
 template <int D, int BQ, int BK>
-int launch(const FwdPtrs &a, const FwdDims &p, int max_row, int which, hipStream_t stream) {
+int launch(const FwdPtrs &a, const FwdDims &p, int which, hipStream_t stream) {
   const long long items = (long long)p.n_work * p.B;
   if (items <= 0) return CALIBATT_OK;
   if (items > 0x7fffffffLL) return CALIBATT_ERR_SHAPE;
   if (a.dtype == CALIBATT_F16)
-    return a.iv ? launch_typed<D, BQ, BK, true, F16>(a, p, max_row, which, stream)
-                : launch_typed<D, BQ, BK, false, F16>(a, p, max_row, which, stream);
-  return a.iv ? launch_typed<D, BQ, BK, true, Bf16>(a, p, max_row, which, stream)
-              : launch_typed<D, BQ, BK, false, Bf16>(a, p, max_row, which, stream);
+    return a.iv ? launch_typed<D, BQ, BK, true, F16>(a, p, which, stream)
+                : launch_typed<D, BQ, BK, false, F16>(a, p, which, stream);
+  return a.iv ? launch_typed<D, BQ, BK, true, Bf16>(a, p, which, stream)
+              : launch_typed<D, BQ, BK, false, Bf16>(a, p, which, stream);
 }
 
 bool strides_ok(const calibatt_strides &t, int B, int H, int N, int D) {
@@ -566,7 +563,7 @@ extern "C" int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const v
   p.out = Strides{out_strides->b, out_strides->h, out_strides->n};
   hipStream_t s = (hipStream_t)stream;
 #define CALIBATT_CASE(d, bq, bk) \
-  if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, pattern->max_row, options->kernel, s);
+  if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, options->kernel, s);
   CALIBATT_CASE(128, 128, 128)
   CALIBATT_CASE(128, 128, 64)
   CALIBATT_CASE(128, 64, 128)

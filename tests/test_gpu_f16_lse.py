@@ -108,7 +108,10 @@ def test_lse_merges_two_gpu_results(lib):
     (o1, l1), (o2, l2), (o, l) = res
     w1, w2 = torch.exp(l1 - l).unsqueeze(-1), torch.exp(l2 - l).unsqueeze(-1)
     merged = w1 * o1 + w2 * o2
-    assert (merged - o).abs().max().item() <= MAX_ABS
+    # o1, o2 and o are each rounded to bf16 (relative half-ulp 2^-9): the merge of two rounded results can
+    # differ from the rounded full result by the kernel's own tolerance plus those three roundings,
+    # 2^-9 (w1 |o1| + w2 |o2| + |o|) <= about 2^-8 |o| for outputs that do not cancel.
+    assert ((merged - o).abs() <= MAX_ABS + 2.0 ** -8 * o.abs()).all().item()
     assert (torch.logaddexp(l1, l2) - l).abs().max().item() <= LSE_ATOL
 
 
