@@ -56,7 +56,7 @@ typedef enum calibatt_status {
   CALIBATT_ERR_REPEAT_RANGE = -4,     /* repeat value outside {-1} U [0, nbq) or self */
   CALIBATT_ERR_REPEAT_CHAIN = -5,     /* source of a repeated block is itself repeated */
   CALIBATT_ERR_REPEAT_TAIL = -6,      /* short last block used as source of a full block */
-  CALIBATT_ERR_BUFFER_TOO_SMALL = -7, /* col_cap < number of kept blocks */
+  CALIBATT_ERR_BUFFER_TOO_SMALL = -7, /* a buffer (col_cap, a workspace, the built-in scratch) is too small */
   CALIBATT_ERR_PATTERN_MISMATCH = -8, /* pattern was compiled for another H/N/block */
   CALIBATT_ERR_LAUNCH = -9,           /* the HIP runtime refused the launch */
   CALIBATT_ERR_NOMEM = -10            /* host scratch allocation failed in compile */
@@ -406,6 +406,26 @@ int calibatt_anchor_partner(int F, int Hs, int Ws, int k, int32_t *partner);
 int calibatt_spatial_similarity(const void *q, const void *k, int B, int H, int N, int D,
                                 const int32_t *partner, int n_tok, int row_len, float scale,
                                 float *workspace, float *score, void *stream);
+
+/*
+ * calibatt_spatial_similarity for callers that cannot allocate device memory
+ * or hand a workspace over (code under HIP graph capture, serving loops that
+ * forbid hipMalloc): the per-token sums live in a buffer inside the library,
+ * CALIBATT_SIMILARITY_STATIC_MAX_BYTES of device memory per GPU that the
+ * library runs on, held until the process ends.  The call allocates nothing.
+ * Arguments and result as calibatt_spatial_similarity without `workspace`.
+ * The buffer keeps the last call's contents (the kernels overwrite every entry
+ * they read, nothing has to be cleared), and every call on a GPU shares it:
+ * calls on one GPU that may overlap (different streams, different host
+ * threads) race on it - serialise them, or use the workspace form.
+ * Errors: as calibatt_spatial_similarity; BUFFER_TOO_SMALL when
+ * B * H * n_tok * 12 bytes exceed the buffer (16 MiB: 40 heads of 34 952
+ * tokens).
+ */
+#define CALIBATT_SIMILARITY_STATIC_MAX_BYTES (16 * 1024 * 1024)
+int calibatt_spatial_similarity_static(const void *q, const void *k, int B, int H, int N, int D,
+                                       const int32_t *partner, int n_tok, int row_len, float scale,
+                                       float *score, void *stream);
 
 /*
  * Calibration steps that turn attention maps into a block mask (Section 3.2).

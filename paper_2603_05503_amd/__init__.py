@@ -33,6 +33,7 @@ from .binding import (  # noqa: F401
     share_timesteps,
     sparse_attn_fwd,
     spatial_similarity,
+    spatial_similarity_static,
     strerror,
     version,
     vote_accumulate,

@@ -127,6 +127,9 @@ def load_library():
     lib.calibatt_spatial_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p,
                                                 C.c_void_p]
+    lib.calibatt_spatial_similarity_static.restype = C.c_int
+    lib.calibatt_spatial_similarity_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                       C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
     lib.calibatt_sparse_attn_fwd_ex.restype = C.c_int
     lib.calibatt_sparse_attn_fwd_ex.argtypes = [
         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -693,4 +696,34 @@ def spatial_similarity(q, k, partner, row_len: int, scale: float, workspace=None
                                          C.c_void_p(stream))
     if st != 0:
         raise CalibattError(st, "calibatt_spatial_similarity")
+    return score
+
+
+SIMILARITY_STATIC_MAX_BYTES = 16 * 1024 * 1024
+
+
+def spatial_similarity_static(q, k, partner, row_len: int, scale: float, score, stream=None):
+    """calibatt_spatial_similarity_static: the call that allocates nothing.  ``score`` is the caller's
+    fp32 CUDA tensor [B, H]; the per-token sums live in the library's own buffer (one per GPU, shared by
+    all calls on it)."""
+    import torch
+
+    lib = load_library()
+    for t in (q, k):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
+            raise ValueError("q, k must be contiguous bf16 CUDA tensors [B, H, N, D]")
+    if q.shape != k.shape:
+        raise ValueError("q and k must have the same shape")
+    if not (partner.is_cuda and partner.dtype == torch.int32 and partner.is_contiguous() and partner.dim() == 1):
+        raise ValueError("partner must be a contiguous 1-d int32 CUDA tensor")
+    B, H, N, D = q.shape
+    if not (score.is_cuda and score.dtype == torch.float32 and score.is_contiguous() and tuple(score.shape) == (B, H)):
+        raise ValueError("score must be a contiguous fp32 CUDA tensor [B, H]")
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = lib.calibatt_spatial_similarity_static(q.data_ptr(), k.data_ptr(), B, H, N, D, partner.data_ptr(),
+                                                partner.numel(), int(row_len), float(scale), score.data_ptr(),
+                                                C.c_void_p(stream))
+    if st != 0:
+        raise CalibattError(st, "calibatt_spatial_similarity_static")
     return score

@@ -257,7 +257,7 @@ extern "C" const char *calibatt_strerror(int status) {
     case CALIBATT_ERR_REPEAT_RANGE: return "repeat map entry out of range or block repeats itself";
     case CALIBATT_ERR_REPEAT_CHAIN: return "source of a repeated block is itself repeated";
     case CALIBATT_ERR_REPEAT_TAIL: return "short last query block used as source of a full block";
-    case CALIBATT_ERR_BUFFER_TOO_SMALL: return "col_idx capacity smaller than the number of kept blocks";
+    case CALIBATT_ERR_BUFFER_TOO_SMALL: return "a caller-provided or built-in buffer is smaller than the call needs";
     case CALIBATT_ERR_PATTERN_MISMATCH: return "pattern was compiled for different H, N or block sizes";
     case CALIBATT_ERR_LAUNCH: return "HIP runtime refused the kernel launch";
     case CALIBATT_ERR_NOMEM: return "host scratch allocation failed";

@@ -313,6 +313,41 @@ extern "C" int calibatt_spatial_similarity(const void *q, const void *k, int B, 
   return launch_similarity<64>((const uint16_t *)q, (const uint16_t *)k, partner, workspace, score, p, s);
 }
 
+// Scratch of calibatt_spatial_similarity_static: one copy per GPU the library runs on, held until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// device address it yields (per device) is what kernels and copies get.
+constexpr long long SIMILARITY_SCRATCH_BYTES = CALIBATT_SIMILARITY_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[SIMILARITY_SCRATCH_BYTES];
+
+namespace {
+std::atomic<void *> scratch_address[64];  // device address of `scratch` on each device, looked up once
+
+int similarity_scratch(void *&ptr) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CALIBATT_ERR_LAUNCH;
+  ptr = scratch_address[dev].load(std::memory_order_acquire);
+  if (ptr) return CALIBATT_OK;
+  void *found = nullptr;
+  if (hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)) != hipSuccess || !found) return CALIBATT_ERR_LAUNCH;
+  scratch_address[dev].store(found, std::memory_order_release);  // concurrent first calls store the same address
+  ptr = found;
+  return CALIBATT_OK;
+}
+}  // namespace
+
+extern "C" int calibatt_spatial_similarity_static(const void *q, const void *k, int B, int H, int N, int D,
+                                                  const int32_t *partner, int n_tok, int row_len, float scale,
+                                                  float *score, void *stream) {
+  if (!q || !k || !partner || !score) return CALIBATT_ERR_NULL;
+  if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || n_tok <= 0 || row_len <= 0 || n_tok > N || n_tok % row_len)
+    return CALIBATT_ERR_SHAPE;
+  if ((long long)B * H * n_tok * 3 * 4 > SIMILARITY_SCRATCH_BYTES) return CALIBATT_ERR_BUFFER_TOO_SMALL;
+  void *workspace = nullptr;
+  if (int st = similarity_scratch(workspace)) return st;
+  return calibatt_spatial_similarity(q, k, B, H, N, D, partner, n_tok, row_len, scale, (float *)workspace, score,
+                                     stream);
+}
+
 extern "C" int calibatt_block_energy(const void *q, const void *k, float *energy, int B, int H, int N, int D,
                                      int block_q, int block_k, float scale, void *stream) {
   if (!q || !k || !energy) return CALIBATT_ERR_NULL;

@@ -43,7 +43,7 @@ def test_header_symbols_exported():
     assert {"calibatt_pattern_sizes", "calibatt_compile_pattern", "calibatt_sparse_attn_fwd",
             "calibatt_anchor_map", "calibatt_anchor_attn_fwd", "calibatt_block_energy", "calibatt_select_blocks",
             "calibatt_vote_masks", "calibatt_vote_accumulate", "calibatt_vote_finish", "calibatt_epsilon_schedule", "calibatt_schedule_base_level",
-            "calibatt_sparse_attn_fwd_strided", "calibatt_sparse_attn_fwd_ex", "calibatt_anchor_attn_fwd_strided", "calibatt_anchor_attn_fwd_split", "calibatt_select_blocks_device", "calibatt_block_energy_onepass", "calibatt_block_energy_workspace_bytes", "calibatt_vote_accumulate_device", "calibatt_anchor_split_plan", "calibatt_anchor_partner", "calibatt_spatial_similarity", "calibatt_encode_intervals", "calibatt_merge_intervals", "calibatt_share_timesteps", "calibatt_strerror", "calibatt_version"} <= names
+            "calibatt_sparse_attn_fwd_strided", "calibatt_sparse_attn_fwd_ex", "calibatt_anchor_attn_fwd_strided", "calibatt_anchor_attn_fwd_split", "calibatt_select_blocks_device", "calibatt_block_energy_onepass", "calibatt_block_energy_workspace_bytes", "calibatt_vote_accumulate_device", "calibatt_anchor_split_plan", "calibatt_anchor_partner", "calibatt_spatial_similarity", "calibatt_spatial_similarity_static", "calibatt_encode_intervals", "calibatt_merge_intervals", "calibatt_share_timesteps", "calibatt_strerror", "calibatt_version"} <= names
     lib = ctypes.CDLL(pkg.library_path())
     for n in names:
         assert hasattr(lib, n), n
