@@ -306,7 +306,7 @@ def sweep(args):
     import torch
 
     import paper_2603_05503_amd as pkg
-    from tests.parity_utils import to_dev
+    from workloads import to_dev
     from workloads import make_workload
 
     if not torch.cuda.is_available():
@@ -376,7 +376,7 @@ def main():
     import torch
 
     import paper_2603_05503_amd as pkg
-    from tests.parity_utils import to_dev
+    from workloads import to_dev
     from workloads import make_workload
 
     if not torch.cuda.is_available():

@@ -99,6 +99,34 @@ def schedule_base_level(N: int) -> float:
     return 0.796 + 1.41e-6 * N
 
 
+def schedule_constants(regime: int, N: int):
+    """(A, C, k) of Eq. 7 as the supplement (Section A.1) gives them.  regime 0: the many-step models,
+    A grows with the sequence length, C = 0.99, k = 16; regime 1: the few-step (distilled) models, one
+    schedule for both resolutions, A = 0.763, C = 0.863, k = 5.64."""
+    if regime == 0:
+        return (0.796 + 1.41e-6 * N, 0.99, 16.0)
+    if regime == 1:
+        return (0.763, 0.863, 5.64)
+    raise ValueError("regime 0 (many-step) or 1 (distilled)")
+
+
+def flag_heads(scores, gamma: float):
+    """Section 3.3: scores[p][h] = spatial similarity score of head h on calibration prompt p.  The
+    scores are averaged over the prompts; a head is flagged as spatially repetitive when its average
+    exceeds gamma.  Returns (flags uint8 [H], means float64 [H]); the mean adds the prompts in order."""
+    rows = [[float(x) for x in row] for row in scores]
+    n, H = len(rows), len(rows[0])
+    means, flags = [], []
+    for h in range(H):
+        total = 0.0
+        for p in range(n):
+            total += rows[p][h]
+        mean = total / n
+        means.append(mean)
+        flags.append(1 if mean > gamma else 0)
+    return np.array(flags, dtype=np.uint8), np.array(means, dtype=np.float64)
+
+
 def vote(masks: np.ndarray, rho: float) -> np.ndarray:
     """Eq. 8-9: masks[p, ...] of |D| prompts -> 1 where the fraction of prompts
     that kept the block is at least rho."""

@@ -150,6 +150,51 @@ def test_schedule_matches_the_numbers_the_paper_prints():
     assert cal.epsilon_schedule(0, 4, 0.763, 0.863, 5.64) == 0.863
 
 
+def test_schedule_constants_of_both_regimes():
+    # supplement A.1 prints both parameter sets; the many-step one reproduces the 0.99 -> 0.84 range of Section 3.2
+    A, C, k = cal.schedule_constants(0, 32760)
+    assert (C, k) == (0.99, 16.0) and A == cal.schedule_base_level(32760)
+    assert round(cal.epsilon_schedule(49, 50, A, C, k), 2) == 0.84
+    A720, _, _ = cal.schedule_constants(0, 75600)
+    assert abs(A720 - (0.796 + 0.106596)) < 1e-12 and A720 > A   # longer sequences keep more energy
+    assert cal.schedule_constants(1, 32760) == (0.763, 0.863, 5.64) == cal.schedule_constants(1, 75600)
+    # the distilled schedule on 4 steps: starts at C, decays towards A, never below it
+    eps = [cal.epsilon_schedule(t, 4, 0.763, 0.863, 5.64) for t in range(4)]
+    assert eps[0] == 0.863 and all(a > b > 0.763 for a, b in zip(eps, eps[1:]))
+    with pytest.raises(ValueError):
+        cal.schedule_constants(2, 100)
+
+
+# ------------------------------------------------------------------ Section 3.3: flagging of repetitive heads
+def test_flag_heads_hand_worked():
+    # three prompts, four heads, gamma = 0.87 (the paper's threshold): means 0.9, 0.87, 0.5, 0.88
+    scores = [[0.95, 0.87, 0.2, 1.00],
+              [0.90, 0.87, 0.9, 0.80],
+              [0.85, 0.87, 0.4, 0.84]]
+    flags, means = cal.flag_heads(scores, 0.87)
+    assert flags.tolist() == [1, 0, 0, 1]          # a mean equal to gamma does not exceed it
+    assert np.allclose(means, [0.9, 0.87, 0.5, 0.88], atol=1e-15)
+    # one prompt: the score itself decides; the mean is not a vote (one low prompt can sink a head)
+    assert cal.flag_heads([[0.871, 0.869]], 0.87)[0].tolist() == [1, 0]
+    assert cal.flag_heads([[1.0], [1.0], [0.5]], 0.87)[0].tolist() == [0]
+    assert cal.flag_heads([[1.0], [1.0], [0.62]], 0.87)[0].tolist() == [1]
+
+
+def test_flag_heads_against_numpy_mean():
+    rng = np.random.default_rng(5)
+    s = rng.uniform(0.5, 1.0, (7, 40))
+    flags, means = cal.flag_heads(s, 0.87)
+    assert np.allclose(means, s.mean(axis=0), rtol=0, atol=1e-15)
+    far = np.abs(s.mean(axis=0) - 0.87) > 1e-12
+    assert (flags[far] == (s.mean(axis=0) > 0.87)[far]).all()
+    # planted mistakes: threshold compared with >=, mean over heads instead of prompts, max instead of mean
+    tie = [[0.87, 0.9], [0.87, 0.8]]
+    assert cal.flag_heads(tie, 0.87)[0].tolist() == [0, 0]
+    assert (np.array(tie).mean(axis=0) >= 0.87).tolist() == [True, False]            # ">=" would flag head 0
+    assert (np.array(tie).max(axis=0) > 0.87).tolist() == [False, True]              # "max" would flag head 1
+    assert (np.array(tie).mean(axis=1) > 0.87).tolist() == [True, False]             # wrong axis gives another answer
+
+
 # ------------------------------------------------------------------ Eq. 8-9
 def test_vote_hand_worked():
     masks = np.array([[[1, 1, 0, 0]], [[1, 0, 1, 0]], [[1, 0, 0, 0]], [[1, 1, 2, 0]]], np.uint8)  # 4 prompts

@@ -1,9 +1,10 @@
 """Seeded synthetic inputs (q/k/v bits, block masks, repeat maps) shared by the
 tests, the benchmark and the CPU oracle's callers.
 
-This package holds input *generation* only: random draws, bf16 rounding of the
-drawn values, mask/repeat-map recipes.  None of the attention arithmetic and
-none of the pattern-compilation logic lives here.
+This package holds input *generation* (random draws, bf16 rounding of the drawn
+values, mask/repeat-map recipes) and the host/GPU plumbing around a run
+(``device.py``).  None of the attention arithmetic and none of the
+pattern-compilation logic lives here.
 """
 from .generators import (  # noqa: F401
     CONFIGS,
@@ -17,4 +18,12 @@ from .generators import (  # noqa: F401
     random_mask,
     sweep_pattern,
     tiny_mask,
+)
+from .device import (  # noqa: F401,E402
+    assert_parity,
+    assert_repeats_bitwise,
+    error_stats,
+    from_dev,
+    run_gpu,
+    to_dev,
 )
