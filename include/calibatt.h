@@ -541,6 +541,29 @@ double calibatt_epsilon_schedule(int t, int T, double A, double C, double k);
 double calibatt_schedule_base_level(int N);
 
 /*
+ * The parameters (A, C, k) of Eq. 7 the paper settles on (supplement,
+ * "Hyperparameter search for energy threshold schedule"), written to *A, *C,
+ * *k.  CALIBATT_REGIME_MANY_STEP: the 50-step models, A =
+ * calibatt_schedule_base_level(N), C = 0.99, k = 16.  CALIBATT_REGIME_DISTILLED:
+ * the few-step (distilled) models, one schedule for every resolution,
+ * A = 0.763, C = 0.863, k = 5.64.  Errors: NULL, SHAPE (N <= 0), UNSUPPORTED
+ * (regime).
+ */
+enum { CALIBATT_REGIME_MANY_STEP = 0, CALIBATT_REGIME_DISTILLED = 1 };
+int calibatt_schedule_constants(int regime, int N, double *A, double *C, double *k);
+
+/*
+ * Which heads are spatially repetitive (Section 3.3): scores (HOST, fp32
+ * [n_prompts][H]) holds the spatial similarity score of every head on every
+ * calibration prompt; the scores of a head are averaged over the prompts (in
+ * double, prompts in order) and flags[h] (HOST, uint8 [H]) is 1 when the
+ * average EXCEEDS gamma (0.87 in the paper), else 0.  mean (HOST, double [H])
+ * receives the averages when not NULL.  Errors: NULL, SHAPE (n_prompts <= 0,
+ * H <= 0, gamma NaN).
+ */
+int calibatt_flag_heads(const float *scores, int n_prompts, int H, double gamma, uint8_t *flags, double *mean);
+
+/*
  * Skip-list tools of the supplement (Section A.2 "Skip-List Memory
  * Optimization", Section A.3 "Timestep Mask Sharing").  All HOST buffers.
  *

@@ -21,12 +21,14 @@ from .binding import (  # noqa: F401
     block_energy_workspace_bytes,
     compile_pattern,
     encode_intervals,
+    flag_heads,
     epsilon_schedule,
     library_path,
     load_library,
     merge_intervals,
     pattern_sizes,
     schedule_base_level,
+    schedule_constants,
     select_blocks,
     select_blocks_device,
     vote_accumulate_device,

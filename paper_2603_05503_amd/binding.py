@@ -121,6 +121,12 @@ def load_library():
         C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
         C.POINTER(_CPattern), C.c_float, C.POINTER(_CStrides), C.POINTER(_CStrides), C.c_void_p,
     ]
+    lib.calibatt_schedule_constants.restype = C.c_int
+    lib.calibatt_schedule_constants.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                                C.POINTER(C.c_double)]
+    lib.calibatt_flag_heads.restype = C.c_int
+    lib.calibatt_flag_heads.argtypes = [C.POINTER(C.c_float), C.c_int, C.c_int, C.c_double, C.POINTER(C.c_uint8),
+                                        C.POINTER(C.c_double)]
     lib.calibatt_anchor_partner.restype = C.c_int
     lib.calibatt_anchor_partner.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, i32p]
     lib.calibatt_spatial_similarity.restype = C.c_int
@@ -313,6 +319,25 @@ class DevicePattern:
         for i in range(9):
             c.group_ptr[i] = int(gp[i])
         self.c = c
+        self._stream_of_c = None   # stream handle that uses self.c
+        self._per_stream = {}      # other streams: (clone of the struct, its own counters)
+
+    def c_for(self, stream_handle: int):
+        """The C struct to pass for a call on ``stream_handle``.  Calls on different streams may overlap on
+        the GPU, and overlapping calls must not share the scheduler's work counters: every stream after the
+        first gets a clone of the struct that points at counters of its own (the index arrays are shared)."""
+        if self.counter is None or self._stream_of_c is None or self._stream_of_c == stream_handle:
+            self._stream_of_c = stream_handle
+            return self.c
+        if stream_handle not in self._per_stream:
+            import torch
+
+            clone = _CPattern()
+            C.memmove(C.byref(clone), C.byref(self.c), C.sizeof(_CPattern))
+            counter = torch.zeros(16, dtype=torch.int32, device=self.counter.device)
+            clone.work_counter = counter.data_ptr()
+            self._per_stream[stream_handle] = (clone, counter)
+        return self._per_stream[stream_handle][0]
 
     @property
     def nnz(self) -> int:
@@ -356,14 +381,14 @@ def sparse_attn_fwd(q, k, v, out, pattern: DevicePattern, scale: float,
     packed = all(t.is_contiguous() for t in (q, k, v, out))
     if packed and lse is None and q.dtype == torch.bfloat16 and kernel == KERNEL_AUTO:
         st = lib.calibatt_sparse_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                                          B, H, N, D, bq, bk, C.byref(pattern.c), float(scale), C.c_void_p(stream))
+                                          B, H, N, D, bq, bk, C.byref(pattern.c_for(int(stream))), float(scale), C.c_void_p(stream))
     else:
         si = _CStrides(q.stride(0), q.stride(1), q.stride(2))
         so = _CStrides(out.stride(0), out.stride(1), out.stride(2))
         opt = _CFwdOptions(None if packed else C.pointer(si), None if packed else C.pointer(so),
                            0 if q.dtype == torch.bfloat16 else 1, None if lse is None else lse.data_ptr(), int(kernel))
         st = lib.calibatt_sparse_attn_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                                             B, H, N, D, bq, bk, C.byref(pattern.c), float(scale),
+                                             B, H, N, D, bq, bk, C.byref(pattern.c_for(int(stream))), float(scale),
                                              C.byref(opt), C.c_void_p(stream))
     if st != 0:
         raise CalibattError(st, "calibatt_sparse_attn_fwd")
@@ -602,6 +627,34 @@ def epsilon_schedule(t: int, T: int, A: float, Cc: float, k: float) -> float:
 
 def schedule_base_level(N: int) -> float:
     return float(load_library().calibatt_schedule_base_level(int(N)))
+
+
+REGIME_MANY_STEP, REGIME_DISTILLED = 0, 1
+
+
+def schedule_constants(regime: int, N: int):
+    """calibatt_schedule_constants: (A, C, k) of Eq. 7 for the many-step (0) or distilled (1) regime."""
+    lib = load_library()
+    A, Cc, k = C.c_double(), C.c_double(), C.c_double()
+    st = lib.calibatt_schedule_constants(int(regime), int(N), C.byref(A), C.byref(Cc), C.byref(k))
+    if st != 0:
+        raise CalibattError(st, "calibatt_schedule_constants")
+    return A.value, Cc.value, k.value
+
+
+def flag_heads(scores, gamma: float):
+    """calibatt_flag_heads: scores [n_prompts, H] -> (flags uint8 [H], mean float64 [H])."""
+    lib = load_library()
+    s = np.ascontiguousarray(scores, dtype=np.float32)
+    if s.ndim != 2:
+        raise ValueError("scores must be [n_prompts, H]")
+    flags = np.zeros(s.shape[1], dtype=np.uint8)
+    mean = np.zeros(s.shape[1], dtype=np.float64)
+    st = lib.calibatt_flag_heads(s.ctypes.data_as(C.POINTER(C.c_float)), int(s.shape[0]), int(s.shape[1]), float(gamma),
+                                 flags.ctypes.data_as(C.POINTER(C.c_uint8)), mean.ctypes.data_as(C.POINTER(C.c_double)))
+    if st != 0:
+        raise CalibattError(st, "calibatt_flag_heads")
+    return flags, mean
 
 
 def encode_intervals(row_ptr, col_idx):

@@ -4,12 +4,24 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstring>
 #include <limits>
 #include <new>
 #include <numeric>
 #include <vector>
 
 #include "calibatt.h"
+
+namespace {
+// Ascending in this key = descending in value, for all finite values and infinities; -0 equals +0.
+inline uint32_t sort_key(float x) {
+  uint32_t u;
+  std::memcpy(&u, &x, 4);
+  if (u == 0x80000000u) u = 0;
+  const uint32_t ascending = (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending in value
+  return ~ascending;
+}
+}  // namespace
 
 extern "C" int calibatt_select_blocks(const float *energy, int64_t n_rows, int nbk, double eps, uint8_t *mask) {
   if (!energy || !mask) return CALIBATT_ERR_NULL;
@@ -24,8 +36,10 @@ extern "C" int calibatt_select_blocks(const float *energy, int64_t n_rows, int n
     const float *e = energy + row * nbk;
     uint8_t *m = mask + row * nbk;
     std::iota(order.begin(), order.end(), 0);
-    // descending energy; among equals the lower column first (stable sort of ascending columns)
-    std::stable_sort(order.begin(), order.end(), [e](int32_t a, int32_t b) { return e[a] > e[b]; });
+    // descending energy; among equals the lower column first (stable sort of ascending columns).
+    // Compared through the order-reversing integer key the device routine sorts by (-0 as +0): a total
+    // order whatever the values, NaN included.
+    std::stable_sort(order.begin(), order.end(), [e](int32_t a, int32_t b) { return sort_key(e[a]) < sort_key(e[b]); });
     std::fill(m, m + nbk, (uint8_t)0);
     double total = 0.0;
     for (int i = 0; i < nbk; ++i) {
@@ -72,3 +86,34 @@ extern "C" double calibatt_epsilon_schedule(int t, int T, double A, double C, do
 }
 
 extern "C" double calibatt_schedule_base_level(int N) { return 0.796 + 1.41e-6 * (double)N; }
+
+extern "C" int calibatt_schedule_constants(int regime, int N, double *A, double *C, double *k) {
+  if (!A || !C || !k) return CALIBATT_ERR_NULL;
+  if (N <= 0) return CALIBATT_ERR_SHAPE;
+  if (regime == CALIBATT_REGIME_MANY_STEP) {
+    *A = calibatt_schedule_base_level(N);
+    *C = 0.99;
+    *k = 16.0;
+  } else if (regime == CALIBATT_REGIME_DISTILLED) {
+    *A = 0.763;
+    *C = 0.863;
+    *k = 5.64;
+  } else {
+    return CALIBATT_ERR_UNSUPPORTED;
+  }
+  return CALIBATT_OK;
+}
+
+extern "C" int calibatt_flag_heads(const float *scores, int n_prompts, int H, double gamma, uint8_t *flags,
+                                   double *mean) {
+  if (!scores || !flags) return CALIBATT_ERR_NULL;
+  if (n_prompts <= 0 || H <= 0 || std::isnan(gamma)) return CALIBATT_ERR_SHAPE;
+  for (int h = 0; h < H; ++h) {
+    double total = 0.0;
+    for (int p = 0; p < n_prompts; ++p) total += (double)scores[(int64_t)p * H + h];
+    const double m = total / (double)n_prompts;
+    if (mean) mean[h] = m;
+    flags[h] = m > gamma ? 1 : 0;
+  }
+  return CALIBATT_OK;
+}

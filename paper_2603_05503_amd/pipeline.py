@@ -1,5 +1,5 @@
 """Calibration and inference stages wired together (paper, Section 3.4) on top of
-the C ABI.  Orchestration only: every computation is a library call.
+the C ABI.  Orchestration only: every computation and every decision is a library call.
 
 ``Calibrator`` collects, per (timestep, layer) key and over calibration prompts,
 the votes of the per-prompt block masks (Section 3.2: block energy, selection at
@@ -75,8 +75,8 @@ class Calibrator:
                 mask, _ = _b.merge_intervals(mask, merge_percentile)
             scores, flagged = None, []
             if key in self._scores:
-                scores = np.stack(self._scores[key]).astype(np.float64).mean(axis=0)  # average over prompts
-                flagged = [h for h in range(self.H) if scores[h] > self.gamma]
+                flags, scores = _b.flag_heads(np.stack(self._scores[key]), self.gamma)  # mean over prompts vs gamma
+                flagged = [h for h in range(self.H) if flags[h]]
             out[key] = CalibrationResult(mask=mask, repetitive_heads=flagged, scores=scores, n_prompts=self._n[key])
         return out
 
@@ -154,9 +154,33 @@ class CalibAttention:
         head_ids = torch.tensor(flagged, dtype=torch.int32, device=self.device) if flagged else None
         self.entries[key] = _Entry(pattern, head_ids, kept, sparse)
 
-    def add_calibrated(self, results: Dict[Hashable, CalibrationResult]) -> None:
+    def add_calibrated(self, results: Dict[Hashable, CalibrationResult], share_tau: Optional[float] = None) -> None:
+        """Adds every calibrated key.  ``share_tau``: timestep mask sharing (supplement A.3).  Keys must
+        then be (timestep, layer) pairs; per layer and head the timesteps are clustered by
+        ``calibatt_share_timesteps`` (IoU of the skipped-block sets >= tau with every member of the
+        cluster) and every member takes the cluster's shared mask.  Keys of a layer whose masks and flagged
+        heads then coincide are stored once: they share one compiled pattern on the GPU."""
+        masks = {key: np.asarray(res.mask, dtype=np.uint8) for key, res in results.items()}
+        if share_tau is not None:
+            layers = sorted({key[1] for key in results})
+            for layer in layers:
+                steps = sorted(key[0] for key in results if key[1] == layer)
+                stack = np.stack([masks[(t, layer)] for t in steps])  # [T, H, nbq, nbk]
+                shared = np.empty_like(stack)
+                for h in range(stack.shape[1]):
+                    cluster, cluster_masks = _b.share_timesteps(stack[:, h], share_tau)
+                    shared[:, h] = cluster_masks[cluster]
+                for i, t in enumerate(steps):
+                    masks[(t, layer)] = shared[i]
+        stored: Dict[Tuple, Hashable] = {}
         for key, res in results.items():
-            self.add(key, res.mask, res.repetitive_heads)
+            layer = key[1] if share_tau is not None else key
+            fingerprint = (layer, tuple(res.repetitive_heads), masks[key].shape, np.packbits(masks[key]).tobytes())
+            if share_tau is not None and fingerprint in stored:
+                self.entries[key] = self.entries[stored[fingerprint]]  # one device pattern for the cluster
+                continue
+            self.add(key, masks[key], res.repetitive_heads)
+            stored[fingerprint] = key
 
     def __call__(self, q, k, v, out, key: Hashable, scale: float, stream=None):
         """One attention call of step/layer ``key``: the sparse forward on the heads of the pattern,
@@ -185,4 +209,11 @@ class CalibAttention:
 
     @property
     def index_bytes(self) -> int:
+        """Bytes of kept-block lists resident on the GPU (a pattern shared by several keys counts once)."""
+        unique = {id(e): e for e in self.entries.values()}
+        return sum(e.pattern.index_bytes for e in unique.values() if e.pattern is not None)
+
+    @property
+    def index_bytes_unshared(self) -> int:
+        """The same with every key holding a pattern of its own."""
         return sum(e.pattern.index_bytes for e in self.entries.values() if e.pattern is not None)

@@ -71,6 +71,40 @@ def test_schedule_matches_oracle_and_paper():
     assert math.isnan(pkg.epsilon_schedule(0, 0, 0.8, 0.99, 16.0))
 
 
+def test_schedule_constants_match_oracle():
+    for regime in (0, 1):
+        for N in (32760, 75600, 44776):
+            assert pkg.schedule_constants(regime, N) == cal.schedule_constants(regime, N)
+    lib = pkg.load_library()
+    d = C.c_double()
+    assert lib.calibatt_schedule_constants(2, 100, C.byref(d), C.byref(d), C.byref(d)) == -3
+    assert lib.calibatt_schedule_constants(0, 0, C.byref(d), C.byref(d), C.byref(d)) == -2
+    assert lib.calibatt_schedule_constants(0, 100, None, C.byref(d), C.byref(d)) == -1
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_flag_heads_matches_oracle(seed):
+    rng = np.random.default_rng(seed)
+    n, H = int(rng.integers(1, 9)), int(rng.integers(1, 50))
+    s = rng.uniform(0.6, 1.0, (n, H)).astype(np.float32)
+    s[:, 0] = np.float32(0.87)  # a head that sits on the threshold (as fp32) on every prompt
+    flags, mean = pkg.flag_heads(s, 0.87)
+    want_flags, want_mean = cal.flag_heads(s, 0.87)
+    assert np.array_equal(flags, want_flags) and np.array_equal(mean, want_mean)
+    lib = pkg.load_library()
+    assert lib.calibatt_flag_heads(None, 1, 1, 0.5, flags.ctypes.data_as(C.POINTER(C.c_uint8)), None) == -1
+    assert lib.calibatt_flag_heads(s.ctypes.data_as(C.POINTER(C.c_float)), 0, 1, 0.5, flags.ctypes.data_as(C.POINTER(C.c_uint8)), None) == -2
+
+
+def test_select_with_nan_energies_is_defined():
+    # the comparator is a total order: NaN entries sort by their bit patterns, nothing is undefined, and rows
+    # without NaN keep their exact masks
+    E = np.array([[0.5, np.nan, 0.3, 0.2], [0.4, 0.3, 0.2, 0.1]], np.float32)
+    m = pkg.select_blocks(E, 0.6)
+    assert m.shape == (2, 4) and set(np.unique(m)) <= {0, 1}
+    assert m[1].tolist() == cal.select_blocks(E[1:2], 0.6)[0].tolist()
+
+
 def test_errors():
     lib = pkg.load_library()
     f32p, u8p = C.POINTER(C.c_float), C.POINTER(C.c_uint8)

@@ -85,3 +85,59 @@ def test_calibrate_then_infer(lib):
         assert max(rel[:2]) < 0.02  # rows repeat exactly: only rounding
         # up to 1 - eps of every row's mass is dropped: eps = 0.99 at step 0, 0.84 at the last step
         assert max(rel[2:]) < (0.08 if key == ("t", 0) else 0.6)
+
+
+def test_timestep_sharing_and_two_streams_on_one_key(lib):
+    """Timestep mask sharing in the resident dictionary (supplement A.3): timesteps whose skipped sets
+    overlap enough take the cluster's OR mask and share one device pattern.  And the same key called on
+    two streams at once (the two guidance branches) gives each call's bits: the wrapper hands every
+    stream scheduler counters of its own."""
+    import torch
+
+    from workloads import random_mask
+
+    print("pipeline sharing", flush=True)
+    Hh, Nn, Dd, blk = 3, 64 * 40 + 17, 64, 64
+    nb = -(-Nn // blk)
+    rng = np.random.default_rng(5)
+    base, _ = random_mask(11, Hh, nb, nb, 0.5, 0.0)
+    results = {}
+    for t in range(6):
+        m = base.copy()
+        if t >= 3:                       # the late steps drop a quarter of the blocks: a second cluster
+            drop = np.random.default_rng(77).random(m.shape) < 0.5
+            m[drop] = 0
+        flip = rng.random(m.shape) < 0.002 * (t % 3)   # small differences inside a cluster
+        m[flip] = 0
+        m[:, np.arange(nb), np.arange(nb)] = 1
+        results[(t, 0)] = lib.CalibrationResult(mask=m, repetitive_heads=[], scores=None, n_prompts=1)
+    att = lib.CalibAttention(Hh, Nn, Dd, blk, blk)
+    att.add_calibrated(results, share_tau=0.9)
+    patterns = {id(att.entries[(t, 0)]) for t in range(6)}
+    assert len(patterns) == 2 and att.entries[(0, 0)] is att.entries[(2, 0)] and att.entries[(3, 0)] is att.entries[(5, 0)]
+    assert att.index_bytes * 3 == att.index_bytes_unshared
+    shared_mask = results[(0, 0)].mask | results[(1, 0)].mask | results[(2, 0)].mask
+    q = f32_to_bf16_bits((2.0 * rng.standard_normal((1, Hh, Nn, Dd))).astype(np.float32))
+    k = f32_to_bf16_bits((2.0 * rng.standard_normal((1, Hh, Nn, Dd))).astype(np.float32))
+    v = f32_to_bf16_bits(rng.standard_normal((1, Hh, Nn, Dd)).astype(np.float32))
+    tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
+    scale = 1 / math.sqrt(Dd)
+    out = torch.empty_like(tq)
+    att(tq, tk, tv, out, (1, 0), scale)
+    torch.cuda.synchronize()
+    want = sparse_attention(q, k, v, shared_mask, None, scale, blk, blk)
+    assert np.abs(bits_to_f64(from_dev(out)) - want).max() <= MAX_ABS
+    serial = out.view(torch.int16).clone()
+    # the same key on two streams at once, several rounds
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = [[torch.empty_like(tq) for _ in range(5)] for _ in range(2)]
+    torch.cuda.synchronize()
+    for r in range(5):
+        for si, st in enumerate((s1, s2)):
+            outs[si][r].view(torch.int16).fill_(0x7FC1)
+            st.wait_stream(torch.cuda.current_stream())
+            att(tq, tk, tv, outs[si][r], (2, 0), scale, stream=st.cuda_stream)
+    torch.cuda.synchronize()
+    for si in range(2):
+        for r in range(5):
+            assert torch.equal(outs[si][r].view(torch.int16), serial), (si, r)
