@@ -65,8 +65,11 @@ def _sample_items(wl, hp, rng, n_min=64):
         rep = np.flatnonzero(wl.repeat[h] >= 0)
         if rep.size:
             items.append((0, int(h), int(rep[rng.integers(rep.size)])))
-    items = sorted(set(items))
-    assert len(items) >= min(n_min, wl.H * wl.nbq) and len({h for _, h, _ in items}) >= min(8, wl.H)
+    items = set(items)
+    while len(items) < min(n_min, wl.H * wl.nbq):  # top up with random rows of the sampled heads
+        items.add((0, int(heads[int(rng.integers(len(heads)))]), int(rng.integers(wl.nbq))))
+    items = sorted(items)
+    assert len({h for _, h, _ in items}) >= min(8, wl.H)
     return items
 
 

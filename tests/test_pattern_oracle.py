@@ -21,13 +21,15 @@ def check_against_worked_example(compile_fn):
     ex = load_worked_example()
     mask = np.array(ex["mask"], dtype=np.uint8)
     repeat = np.array(ex["repeat"], dtype=np.int32)
-    for order in (0, 1, 2):
+    for order in (0, 1, 2, 3, 4):
         p = compile_fn(mask, repeat, ex["H"], ex["N"], ex["block_q"], ex["block_k"], order)
         assert (p["nnz"], p["n_work"], p["n_repeat"]) == (ex["nnz"], ex["n_work"], ex["n_repeat"])
         for name in ("row_ptr", "col_idx", "repeat_src"):
             assert p[name].tolist() == ex[name], (order, name)
         for name in ("work", "fan_ptr", "fan_dst"):
             assert p[name].tolist() == ex[f"order{order}"][name], (order, name)
+        if order >= 3:  # the groups of the XCD-aware orders
+            assert np.asarray(p["group_ptr"]).tolist() == ex[f"order{order}"]["group_ptr"], order
 
 
 def independent_numpy_compile(mask, repeat, H, N, bq, bk, order):
