@@ -11,8 +11,10 @@ HBM.  The metric is computed-block bf16 TFLOP/s = kept blocks * 4*bq*bk*D / t.
 Prints ONE JSON line: the headline metric with its roofline object (MFMA bound,
 achieved by HIP events, traffic from the committed rocprofv3 summary), the dense
 reference run of the same kernel, the clock the GPU sustained, the CPU oracle
-baseline, and side tables for the anchor-row path (the k of the paper's table),
-the block-energy kernel and the spatial similarity kernel.  ``--sweep`` runs the
+baseline, compact legs for the other named configurations (Tiny, Wan-720p at
+15 / 30 / 60 / 100 %, Mochi) and a 200-launch subset of the full step sweep,
+and side tables for the anchor-row path (the k of the paper's table), the
+block-energy kernel and the spatial similarity kernel.  ``--sweep`` runs the
 full step sweep instead (one pattern per layer and timestep).
 """
 from __future__ import annotations
@@ -59,6 +61,9 @@ def parse_args():
                     help="skip the MFMA-only probe (zero vs random operands) that gives the practical ceiling")
     ap.add_argument("--no-anchor", action="store_true", help="skip the spatial-row anchor table")
     ap.add_argument("--no-energy", action="store_true", help="skip the calibration kernels (block energy, spatial similarity)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the compact legs for the other named configurations and the sweep subset")
+    ap.add_argument("--sweep-subset", type=int, default=200, help="patterns in the default run's sweep subset")
     ap.add_argument("--kernel", default="auto", choices=["auto", "2wg", "il"],
                     help="schedule of the forward (the `kernel` field of calibatt_fwd_options): the library's "
                          "choice, the two-workgroup kernel, or the interleaved kernel")
@@ -250,8 +255,11 @@ def cpu_oracle_baseline(wl, n_blocks):
     sparse_attention_blocks(wl.q, wl.k, wl.v, wl.mask, wl.repeat, wl.scale, wl.block_q, wl.block_k, items)
     dt = time.perf_counter() - t0
     flops = kept * 4.0 * wl.block_q * wl.block_k * wl.D
+    total_kept = int(wl.mask[wl.repeat < 0].astype(bool).sum()) * wl.B
     return {
         "value": flops / dt / 1e12,
+        # the whole launch at the sample's rate (sample seconds x kept blocks of the launch / kept blocks of the sample)
+        "extrapolated_full_shape_seconds": dt * total_kept / max(kept, 1),
         "unit": "TFLOP/s",
         "cores": int(threads),
         "kind": "oracle",
@@ -262,19 +270,103 @@ def cpu_oracle_baseline(wl, n_blocks):
 
 
 def profiled_traffic(args):
-    """HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this
-    exact command line (default workload and schedule); None for anything else."""
+    """(HBM-side bytes per launch, where the figure comes from).  Hardware counters cannot be read from
+    inside this process, so the figure is NOT measured in this run: it is the one the committed rocprofv3
+    --pmc summary of this exact command line (default workload, schedule and kernel) holds, together with
+    that file's name and the source revision it names.  (None, reason) for any other command line."""
     if args.workload != "wan480" or args.density is not None or args.repeat_frac is not None \
-            or args.heads is not None or args.order != 4 or args.no_persistent or args.intervals:
-        return None
+            or args.heads is not None or args.order != 4 or args.no_persistent or args.intervals or args.kernel != "auto":
+        return None, "not profiled for these arguments"
     path = os.path.join(ROOT, "profiles", "sparse_attn_fwd_wan480.txt")
+    traffic, revision = None, "unknown revision"
     try:
         for line in open(path):
             if line.startswith("roofline.traffic"):
-                return float(line.split("=")[1])
+                traffic = float(line.split("=")[1])
+            if line.startswith("measured at"):
+                revision = line.strip()
     except OSError:
-        pass
-    return None
+        return None, "profiles/sparse_attn_fwd_wan480.txt missing"
+    return traffic, f"profiles/sparse_attn_fwd_wan480.txt (rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE, {revision}); not re-measured in this run"
+
+
+def config_legs(pkg, torch, steps, kernel):
+    """The other named configurations, compact: Tiny, Wan-720p at 15 / 30 / 60 % (20 % repeats) with its
+    all-ones reference, Mochi.  Masks and repeat maps from the seeded generator; q, k, v are N(0,1) bf16
+    drawn on the GPU (seeded) - the timing does not depend on where the values come from, and the parity
+    of these shapes is what tests/test_gpu_fullsize.py checks with the generator's own tensors."""
+    from workloads import make_workload
+
+    legs = {}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20260305)
+    tensors = {}
+
+    def qkv(wl):
+        key = (wl.B, wl.H, wl.N, wl.D)
+        if key not in tensors:
+            tensors.clear()
+            torch.cuda.empty_cache()
+            tensors[key] = [torch.randn(key, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                            for _ in range(3)] + [torch.empty(key, device="cuda", dtype=torch.bfloat16)]
+        return tensors[key]
+
+    def timed(wl, n):
+        hp = pkg.compile_pattern(wl.mask, wl.repeat, wl.H, wl.N, wl.block_q, wl.block_k, 4)
+        dp = hp.to_device()
+        q, k, v, out = qkv(wl)
+        _, ms, _ = time_launches(pkg, torch, q, k, v, out, dp, wl.scale, n, 1, kernel)
+        return ms, hp.nnz * wl.B * 4.0 * wl.block_q * wl.block_k * wl.D
+
+    plan = [("tiny", "tiny", None), ("wan720_15", "wan720", 0.15), ("wan720_30", "wan720", 0.30),
+            ("wan720_60", "wan720", 0.60), ("mochi_25", "mochi", None)]
+    dense_ms = {}
+    for tag, name, density in plan:
+        wl = make_workload(name, density=density, with_qkv=False)
+        ms, flops = timed(wl, steps)
+        if name not in dense_ms:
+            wd = make_workload(name, dense=True, with_qkv=False)
+            dense_ms[name] = timed(wd, max(2, steps // 3))
+        d_ms, d_flops = dense_ms[name]
+        tf = flops / (ms * 1e-3) / 1e12
+        legs[tag] = {"workload": f"{name}: B={wl.B} H={wl.H} N={wl.N} D={wl.D} blocks {wl.block_q}x{wl.block_k}, "
+                                 f"density {wl.stats.get('density', 0):.3f}, repeated {wl.stats.get('repeat_frac', 0):.3f}",
+                     "ms": ms, "tflops": tf, "frac_of_bf16_mfma_peak": tf / PEAK_BF16_TFLOPS,
+                     "dense_ms": d_ms, "dense_tflops": d_flops / (d_ms * 1e-3) / 1e12, "speedup_sparse_vs_dense": d_ms / ms}
+    tensors.clear()
+    torch.cuda.empty_cache()
+    return legs
+
+
+def sweep_subset_leg(pkg, torch, q, k, v, out, wl, n_patterns, kernel):
+    """A seeded subset of the full step sweep (Wan-480p shape, one pattern per (layer, timestep), density
+    ~ U(0.1, 0.6), repeat fraction ~ U(0, 0.3)): every 10th of the 2000 (layer, timestep) pairs in
+    timestep-major order, compiled up front, uploaded in interval form, launched back to back."""
+    import multiprocessing as mp
+
+    pairs = [(l, t) for t in range(50) for l in range(40)][:: max(1, 2000 // n_patterns)][:n_patterns]
+    t0 = time.perf_counter()
+    with mp.get_context("spawn").Pool(min(16, os.cpu_count() or 1)) as pool:
+        built = pool.map(_sweep_compile, [(l, t, wl.H, 4) for l, t in pairs], chunksize=2)
+    build_s = time.perf_counter() - t0
+    patterns = [hp.to_device(intervals=True) for _, _, hp, _, _ in built]
+    nnz = sum(hp.nnz for _, _, hp, _, _ in built)
+    for dp in patterns[:3]:
+        pkg.sparse_attn_fwd(q, k, v, out, dp, wl.scale, kernel=kernel)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for dp in patterns:
+        pkg.sparse_attn_fwd(q, k, v, out, dp, wl.scale, kernel=kernel)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    tf = nnz * wl.B * 4.0 * wl.block_q * wl.block_k * wl.D / wall / 1e12
+    dens = [d for *_, d, _ in built]
+    return {"subset": f"{len(pairs)} of the 2000 (layer, timestep) patterns: every {max(1, 2000 // n_patterns)}th pair in "
+                      "timestep-major order", "launches": len(pairs), "total_ms": wall * 1e3,
+            "ms_per_launch": wall * 1e3 / len(pairs), "tflops": tf, "frac_of_bf16_mfma_peak": tf / PEAK_BF16_TFLOPS,
+            "extrapolated_2000_launches_s": wall * 2000 / len(pairs), "density_mean": sum(dens) / len(dens),
+            "pattern_form": "intervals", "pattern_index_bytes": int(sum(dp.index_bytes for dp in patterns)),
+            "pattern_build_s_cpu_pool": build_s}
 
 
 def _sweep_compile(job):
@@ -426,6 +518,7 @@ def main():
             observed = {"sclk_mhz": mhz, "mfma_peak_at_that_clock_tflops": peak_at_clock,
                         "frac_of_peak_at_that_clock": achieved / peak_at_clock}
 
+    traffic, traffic_source = profiled_traffic(args)
     result = {
         "metric": "computed-block bf16 TFLOP/s (% MFMA peak); speedup vs dense @ Wan 480p shape",
         "value": value,
@@ -463,7 +556,8 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS,
-            "traffic": profiled_traffic(args),
+            "traffic": traffic,
+            "traffic_source": traffic_source,
         },
     }
     if probe:
@@ -476,6 +570,11 @@ def main():
         result["block_energy"] = energy_leg(pkg, torch, q, k, wl, max(3, args.steps // 4))
         if getattr(wl, "geometry", None) is not None:
             result["spatial_similarity"] = similarity_leg(pkg, torch, q, k, wl, max(3, args.steps // 4))
+    if not args.no_configs:
+        result["sweep_subset"] = sweep_subset_leg(pkg, torch, q, k, v, out, wl, args.sweep_subset, KERNELS[args.kernel])
+        del q, k, v, out
+        torch.cuda.empty_cache()
+        result["configs"] = config_legs(pkg, torch, max(3, args.steps // 4), KERNELS[args.kernel])
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_oracle_baseline(wl, args.cpu_blocks)
     print(json.dumps(result))
