@@ -40,16 +40,6 @@ fan_ptr[n_work+1], fan_dst[n_repeat]
                     for work item i the ascending list of blocks r' of the same
                     head with repeat[h, r'] == r.
 
-item records [n_work][8] (pack_items)
-                    everything the forward needs to start work item i, in one
-                    place, so that a workgroup can fetch the next item's row
-                    with a single read while it still computes the current one:
-                    word 0 id = h*nbq + r; 1 row_ptr[id]; 2 kept count of the
-                    row; 3 fan_ptr[i]; 4 fan_ptr[i+1]; 5 the row's first kept
-                    column (0 for a row that keeps nothing); 6, 7 iv_ptr[id],
-                    iv_ptr[id+1] of the interval form (Section A.2 of the
-                    supplement), both 0 when the pattern has none.
-
 Rejected inputs (exceptions here, status codes in the library):
  range : repeat value outside {-1} U [0, nbq), or a block repeating itself
  chain : the source of a repeated block is itself repeated
@@ -170,16 +160,3 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
         work=i32(work), fan_ptr=i32(fan_ptr), fan_dst=i32(fan_dst),
         n_groups=N_GROUPS if order in (3, 4) else 1, group_ptr=i32(group_ptr),
     )
-
-
-def pack_items(pattern, iv_ptr=None):
-    """Item records of a compiled pattern (dict returned by compile_pattern); ``iv_ptr`` is the
-    row offset array of the interval form, if the pattern is to be used with one."""
-    rows = []
-    for i, rid in enumerate(pattern["work"]):
-        rid = int(rid)
-        begin, end = int(pattern["row_ptr"][rid]), int(pattern["row_ptr"][rid + 1])
-        first = int(pattern["col_idx"][begin]) if end > begin else 0
-        iv = (0, 0) if iv_ptr is None else (int(iv_ptr[rid]), int(iv_ptr[rid + 1]))
-        rows.append([rid, begin, end - begin, int(pattern["fan_ptr"][i]), int(pattern["fan_ptr"][i + 1]), first, iv[0], iv[1]])
-    return np.asarray(rows, dtype=np.int32).reshape(-1, 8)

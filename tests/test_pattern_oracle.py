@@ -6,8 +6,7 @@ import os
 import numpy as np
 import pytest
 
-from oracle import PatternError, compile_pattern, pack_items, pattern_sizes
-from oracle.skiplist import encode_intervals
+from oracle import PatternError, compile_pattern, pattern_sizes
 from workloads import random_mask
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -31,32 +30,6 @@ def check_against_worked_example(compile_fn):
             assert p[name].tolist() == ex[f"order{order}"][name], (order, name)
         if order >= 3:  # the groups of the XCD-aware orders
             assert np.asarray(p["group_ptr"]).tolist() == ex[f"order{order}"]["group_ptr"], order
-
-
-def kept_rows(mask, repeat):
-    """Mask rows as the compiled pattern keeps them: a repeated block keeps nothing."""
-    m = (np.asarray(mask) != 0).astype(np.uint8)
-    m[np.asarray(repeat) >= 0] = 0
-    return m.reshape(-1, m.shape[-1])
-
-
-def check_items_against_worked_example(pack_fn):
-    """pack_fn(mask, repeat, H, N, bq, bk, order, with_intervals) -> int32 [n_work, 8]."""
-    ex = load_worked_example()
-    mask = np.array(ex["mask"], dtype=np.uint8)
-    repeat = np.array(ex["repeat"], dtype=np.int32)
-    want = np.array(ex["order4"]["items"], dtype=np.int32)
-    got = pack_fn(mask, repeat, ex["H"], ex["N"], ex["block_q"], ex["block_k"], 4, True)
-    assert np.asarray(got).tolist() == want.tolist()
-    want[:, 6:] = 0  # no interval form: the two offsets are zero
-    got = pack_fn(mask, repeat, ex["H"], ex["N"], ex["block_q"], ex["block_k"], 4, False)
-    assert np.asarray(got).tolist() == want.tolist()
-
-
-def oracle_pack(mask, repeat, H, N, bq, bk, order, with_intervals):
-    p = compile_pattern(mask, repeat, H, N, bq, bk, order)
-    iv_ptr = encode_intervals(kept_rows(mask, repeat))[0] if with_intervals else None
-    return pack_items(p, iv_ptr)
 
 
 def independent_numpy_compile(mask, repeat, H, N, bq, bk, order):
@@ -177,37 +150,6 @@ def check_invariants(p, mask, repeat, H, N, bq, bk, order):
             assert w.max() - w.min() <= max(per_head.values())
     else:
         assert p["n_groups"] == 1 and p["group_ptr"][0] == 0 and p["group_ptr"][1] == p["n_work"]
-
-
-def test_oracle_item_records_worked_example():
-    ex = load_worked_example()
-    rows = kept_rows(np.array(ex["mask"]), np.array(ex["repeat"]))
-    assert encode_intervals(rows)[0].tolist() == ex["iv_ptr"]
-    check_items_against_worked_example(oracle_pack)
-
-
-@pytest.mark.parametrize("seed", [0, 1, 2])
-@pytest.mark.parametrize("order", [0, 3, 4])
-def test_oracle_item_records_properties(seed, order):
-    """Every record restates the arrays it was gathered from (vectorised second construction)."""
-    H, nbq, nbk = 3, 9, 9
-    mask, repeat = random_mask(seed + 40, H, nbq, nbk, 0.3, 0.25)
-    mask[1, 2] = 0  # a computed row that keeps nothing
-    repeat[1, 2] = -1
-    p = compile_pattern(mask, repeat, H, nbq * 16, 16, 16, order)
-    iv_ptr = encode_intervals(kept_rows(mask, repeat))[0]
-    rec = pack_items(p, iv_ptr)
-    ids = p["work"].astype(np.int64)
-    assert rec.shape == (p["n_work"], 8) and rec.dtype == np.int32
-    assert (rec[:, 0] == ids).all()
-    assert (rec[:, 1] == p["row_ptr"][ids]).all()
-    assert (rec[:, 2] == np.diff(p["row_ptr"])[ids]).all()
-    assert (rec[:, 3] == p["fan_ptr"][:-1]).all() and (rec[:, 4] == p["fan_ptr"][1:]).all()
-    dense_rows = kept_rows(mask, repeat)[ids]
-    first = np.where(dense_rows.any(axis=1), dense_rows.argmax(axis=1), 0)
-    assert (rec[:, 5] == first).all()
-    assert (rec[:, 6] == iv_ptr[ids]).all() and (rec[:, 7] == iv_ptr[ids + 1]).all()
-    assert (pack_items(p)[:, :6] == rec[:, :6]).all() and (pack_items(p)[:, 6:] == 0).all()
 
 
 def test_oracle_worked_example():
