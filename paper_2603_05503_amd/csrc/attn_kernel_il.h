@@ -56,13 +56,20 @@ constexpr int IL_VGPRS = 72;  // arch VGPRs left to the compiler; the named ones
 constexpr int IL_STAGES = 6;  // operand staging slots
 constexpr int IL_AHEAD = 4;   // MFMAs between the issue of an operand's LDS reads and its use
 
+// Keys per sub-tile for a key block of BK keys: the block is a whole number of sub-tiles (two for
+// the power-of-two widths; three or five for 96, 160 and 192).
+constexpr __host__ __device__ int il_sub(int bk) { return bk >= 128 && bk % 64 == 0 ? 64 : 32; }
+
+// The base class lays out LDS and lanes for a window of two sub-tiles of K and of V.
 template <int D, int BQ, int BK, typename T = Bf16>
-struct IlRow : RowBlock<D, BQ, BK, T> {
-  using RB = RowBlock<D, BQ, BK, T>;
+struct IlRow : RowBlock<D, BQ, 2 * il_sub(BK), T> {
+  using RB = RowBlock<D, BQ, 2 * il_sub(BK), T>;
   using RB::DB;
   using RB::DS;
   using RB::ROWB;
-  static constexpr int SUB = BK / 2;             // keys per sub-tile
+  static constexpr int SUB = il_sub(BK);         // keys per sub-tile
+  static constexpr int SPB = BK / SUB;           // sub-tiles per key block
+  static_assert(BK % SUB == 0 && SPB >= 2, "a key block is a whole number of sub-tiles");
   static constexpr int KBS = SUB / 32;           // 32-key sub-blocks per sub-tile
   static_assert(KBS >= 1, "sub-tiles of at least 32 keys");
   static constexpr int EL = 16 * KBS;            // S^T elements per lane and sub-tile
@@ -396,73 +403,91 @@ __global__ __launch_bounds__(BQ * 2, (BQ >= 128 ? 2 : 1)) __attribute__((amdgpu_
     }
 
     if (n_tiles > 0) {
-      // Sub-tile u_k = half k & 1 of the row's kept block k >> 1.  Stage k: O += P V of u_(k-2),
-      // S = K Q^T of u_k, softmax of u_(k-1); at its start the loads of V of u_(k-1) and K of u_(k+1)
-      // are issued into the slots the stage before has finished with, and they land by its end.
-      const int n_sub = 2 * n_tiles;
-      const bool ragged = (N % BK) != 0;
-      int c0 = col_of(0);
-      rb.issue_k_sub(Kres, c0 * BK, 0);
+      // The row's kept blocks as a stream of sub-tiles u_0, u_1, ... (SPB per block, an odd total is
+      // padded with one sub-tile beyond the sequence, all of whose keys are masked).  Stage k:
+      // O += P V of u_(k-2), S = K Q^T of u_k, softmax of u_(k-1); at its start the loads of V of u_(k-1)
+      // and K of u_(k+1) are issued into the slots the stage before has finished with, and they land by
+      // its end.  Stages alternate between the two slots of the windows and the two S buffers.
+      constexpr int SPB = Row::SPB;
+      const int n_sub = n_tiles * SPB;
+      const int n_stream = (n_sub + 1) & ~1;
+      // First key row of the next sub-tile of the stream (N beyond its end: rows there read as zeros
+      // and the keys are masked); called once per sub-tile, in order.
+      int nx_entry = 0, nx_part = 0, nx_col = col_of(0);
+      auto next_rows = [&]() {
+        if (nx_entry >= n_tiles) return N;
+        const int row0 = nx_col * BK + nx_part * SUB;
+        if (++nx_part == SPB) {
+          nx_part = 0;
+          ++nx_entry;
+          if ((nx_entry & 63) == 0 && nx_entry < n_tiles) {
+            if constexpr (IV) {
+              if (nx_entry % IV_COLS == 0) {  // every wave has taken its entries of the chunk that is replaced
+                chunk_lo = nx_entry;
+                expand_runs();
+              }
+            }
+            col_cache = col_at(min(nx_entry + lane, n_tiles - 1));
+          }
+          if (nx_entry < n_tiles) nx_col = col_of(nx_entry);
+        }
+        return row0;
+      };
+      // keys of a sub-tile that starts at key row row0 and lie beyond the sequence get -inf
+#define CALIBATT_IL_MASK(PAR, row0) \
+  if ((row0) + SUB > N) rb.template mask_tail<PAR>(N - (row0) - 8 * rb.g);
+      const int r0 = next_rows();
+      rb.issue_k_sub(Kres, r0, 0);
       wait_vmem<0>();
       __syncthreads();
       // stage 0: K of u_1 streams in; S of u_0
-      rb.issue_k_sub(Kres, c0 * BK + SUB, 1);
+      const int r1 = next_rows();
+      rb.issue_k_sub(Kres, r1, 1);
       rb.template stage<0, false, true, false>();
-      if (ragged && c0 == p.nbk - 1) rb.template mask_tail<0>(N - c0 * BK - 8 * rb.g);
+      CALIBATT_IL_MASK(0, r0)
       wait_vmem<0>();
       __syncthreads();
       // stage 1: V of u_0, K of u_2; S of u_1, softmax of u_0
-      int c_prev = c0;  // block of u_(k-1) at the start of stage k (k even below)
-      rb.issue_v_sub(Vres, c0 * BK, 0);
-      int c1 = n_tiles > 1 ? col_of(1) : c0;
-      if (n_tiles > 1) rb.issue_k_sub(Kres, c1 * BK, 0);
+      rb.issue_v_sub(Vres, r0, 0);
+      int row_a = r1;            // of u_(k-1) at the start of stage k (k even below)
+      int row_b = next_rows();   // of u_k
+      rb.issue_k_sub(Kres, row_b, 0);
       rb.template stage<1, false, true, true>();
-      if (ragged && c0 == p.nbk - 1) rb.template mask_tail<1>(N - c0 * BK - SUB - 8 * rb.g);
+      CALIBATT_IL_MASK(1, r1)
       wait_vmem<0>();
       __syncthreads();
-      for (int t = 1; t < n_tiles; ++t) {
-        // stages 2t and 2t+1: block c = entry t of the list, c_prev = entry t-1, c_nx = entry t+1
-        const int c = c1;
-        if (((t + 1) & 63) == 0 && t + 1 < n_tiles) {
-          if constexpr (IV) {
-            if ((t + 1) % IV_COLS == 0) {  // every wave has taken its entries of the chunk that is replaced
-              chunk_lo = t + 1;
-              expand_runs();
-            }
-          }
-          col_cache = col_at(min(t + 1 + lane, n_tiles - 1));
-        }
-        const int c_nx = t + 1 < n_tiles ? col_of(t + 1) : c;
-        // loads inside the stream: V of u_(2t-1), K of u_(2t+1)
+      for (int k = 2; k < n_stream; k += 2) {
+        // stage k: loads inside the stream: V of u_(k-1), K of u_(k+1)
+        const int row_c = next_rows();
         IL_PROF(3);
-        rb.template stage<0, true, true, true, true>(Vres, c_prev * BK + SUB, Kres, c * BK + SUB);
+        rb.template stage<0, true, true, true, true>(Vres, row_a, Kres, row_c);
         IL_PROF(0);
-        if (ragged && c == p.nbk - 1) rb.template mask_tail<0>(N - c * BK - 8 * rb.g);
+        CALIBATT_IL_MASK(0, row_b)
         wait_vmem<0>();
         IL_PROF(1);
         __syncthreads();
         IL_PROF(2);
-        // loads inside the stream: V of u_(2t), K of u_(2t+2) (after the row's last block: that block's K
-        // once more, into a slot nobody reads)
+        // stage k + 1: V of u_k, K of u_(k+2) (beyond the stream: zeros into a slot nobody reads)
+        const int row_d = next_rows();
         IL_PROF(3);
-        rb.template stage<1, true, true, true, true>(Vres, c * BK, Kres, c_nx * BK);
+        rb.template stage<1, true, true, true, true>(Vres, row_b, Kres, row_d);
         IL_PROF(0);
-        if (ragged && c == p.nbk - 1) rb.template mask_tail<1>(N - c * BK - SUB - 8 * rb.g);
+        CALIBATT_IL_MASK(1, row_c)
         wait_vmem<0>();
         IL_PROF(1);
         __syncthreads();
         IL_PROF(2);
-        c_prev = c;
-        c1 = c_nx;
+        row_a = row_c;
+        row_b = row_d;
       }
-      // stage n_sub: V of the last sub-tile; O += P V of u_(n_sub-2), softmax of u_(n_sub-1)
-      rb.issue_v_sub(Vres, c_prev * BK + SUB, 1);
+#undef CALIBATT_IL_MASK
+      // stage n_stream: V of the last sub-tile; O += P V of u_(n_stream-2), softmax of u_(n_stream-1)
+      rb.issue_v_sub(Vres, row_a, 1);
       rb.template stage<0, true, false, true>();
       wait_vmem<0>();
       __syncthreads();
-      // stage n_sub + 1: O += P V of u_(n_sub-1)
+      // stage n_stream + 1: O += P V of u_(n_stream-1)
       rb.template stage<1, true, false, false>();
-      (void)n_sub;
     }
 
     // ---- normalise, stage in LDS, store to the block and its repeat targets ----

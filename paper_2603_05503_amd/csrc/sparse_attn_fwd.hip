@@ -101,11 +101,15 @@ int launch_typed(const FwdPtrs &a, const FwdDims &p, int which, hipStream_t stre
     if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
     return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
   }
-  static DevInfo info;
-  constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + (IV ? IV_COLS * 4 : 0);
-  auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, IV, T>;
-  if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
-  return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
+  if constexpr (BK == 64 || BK == 128) {
+    static DevInfo info;
+    constexpr int SMEM = RowBlock<D, BQ, BK>::LDS_BYTES + 64 + (IV ? IV_COLS * 4 : 0);
+    auto kernel = sparse_attn_fwd_kernel<D, BQ, BK, IV, T>;
+    if (int st = prepare(kernel, BQ * 2, SMEM, info, slots)) return st;
+    return enqueue(kernel, BQ * 2, SMEM, slots, a, p, stream);
+  } else {
+    return CALIBATT_ERR_UNSUPPORTED;  // the two-workgroup kernel is built for key blocks of 64 and 128 only
+  }
 }
 
 template <int D, int BQ, int BK>
@@ -368,6 +372,9 @@ extern "C" int calibatt_block_energy(const void *q, const void *k, float *energy
   if (D == d && block_q == bq && block_k == bk) return launch_energy<d, bq, bk>(qq, kk, energy, p, s);
   CALIBATT_CASE(128, 128, 128)
   CALIBATT_CASE(128, 128, 64)
+  CALIBATT_CASE(128, 128, 96)
+  CALIBATT_CASE(128, 128, 160)
+  CALIBATT_CASE(128, 128, 192)
   CALIBATT_CASE(128, 64, 128)
   CALIBATT_CASE(128, 64, 64)
   CALIBATT_CASE(64, 128, 128)
@@ -409,6 +416,9 @@ extern "C" int calibatt_block_energy_onepass(const void *q, const void *k, float
     return launch_energy_onepass<d, bq, bk>(qq, kk, energy, p, (float *)workspace, workspace_bytes, s);
   CALIBATT_CASE(128, 128, 128)
   CALIBATT_CASE(128, 128, 64)
+  CALIBATT_CASE(128, 128, 96)
+  CALIBATT_CASE(128, 128, 160)
+  CALIBATT_CASE(128, 128, 192)
   CALIBATT_CASE(128, 64, 128)
   CALIBATT_CASE(128, 64, 64)
   CALIBATT_CASE(64, 128, 128)
@@ -546,7 +556,8 @@ extern "C" int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const v
   if (options->lse && ((uintptr_t)options->lse & 3)) return CALIBATT_ERR_SHAPE;
   if (!q || !k || !v || !out || !pattern) return CALIBATT_ERR_NULL;
   if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || block_q <= 0 || block_k <= 0) return CALIBATT_ERR_SHAPE;
-  if (!(D == 64 || D == 128) || !(block_q == 64 || block_q == 128) || !(block_k == 64 || block_k == 128))
+  const bool wide_keys = D == 128 && block_q == 128 && (block_k == 96 || block_k == 160 || block_k == 192);
+  if (!(D == 64 || D == 128) || !(block_q == 64 || block_q == 128) || !(block_k == 64 || block_k == 128 || wide_keys))
     return CALIBATT_ERR_UNSUPPORTED;
   if (out == q || out == k || out == v) return CALIBATT_ERR_SHAPE;
   const int nbq = (N + block_q - 1) / block_q, nbk = (N + block_k - 1) / block_k;
@@ -601,6 +612,9 @@ extern "C" int calibatt_sparse_attn_fwd_ex(const void *q, const void *k, const v
   if (D == d && block_q == bq && block_k == bk) return launch<d, bq, bk>(a, p, options->kernel, s);
   CALIBATT_CASE(128, 128, 128)
   CALIBATT_CASE(128, 128, 64)
+  CALIBATT_CASE(128, 128, 96)
+  CALIBATT_CASE(128, 128, 160)
+  CALIBATT_CASE(128, 128, 192)
   CALIBATT_CASE(128, 64, 128)
   CALIBATT_CASE(128, 64, 64)
   CALIBATT_CASE(64, 128, 128)

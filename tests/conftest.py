@@ -20,18 +20,18 @@ def lib():
     return pkg
 
 
-@pytest.fixture(params=["auto", "2wg", "il"])
+@pytest.fixture(params=["auto", "2wg"])
 def kernel_variant(request, monkeypatch):
-    """Runs a GPU test once per schedule of the forward: the library's own choice, the
-    two-workgroup kernel forced, and the interleaved kernel forced wherever it applies (calls it
-    does not cover take the library's choice)."""
+    """Runs a GPU test once per schedule of the forward: the library's own choice (the interleaved
+    kernel) and the two-workgroup kernel forced wherever it applies (calls it does not cover take
+    the library's choice)."""
     import paper_2603_05503_amd as pkg
     from paper_2603_05503_amd import binding
 
     if request.param == "auto":
         return request.param
     plain = binding.sparse_attn_fwd
-    forced = binding.KERNEL_TWO_WORKGROUPS if request.param == "2wg" else binding.KERNEL_INTERLEAVED
+    forced = binding.KERNEL_TWO_WORKGROUPS
 
     def variant(q, k, v, out, pattern, scale, *args, **kwargs):
         if "kernel" in kwargs:

@@ -43,6 +43,9 @@ def _both(lib, q, k, v, hp, scale, persistent=True):
     (1, 2, 1000, 64, 128, 64, 0.5, 0.3),
     (1, 1, 700, 128, 128, 128, 0.0, 0.0),   # only the forced diagonal
     (1, 1, 700, 128, 128, 128, 1.0, 0.0),   # one run per row
+    (1, 2, 1500, 128, 128, 96, 0.4, 0.2),   # three sub-tiles per key block
+    (1, 2, 1500, 128, 128, 160, 0.4, 0.2),  # five
+    (1, 2, 1500, 128, 128, 192, 0.4, 0.0),
 ])
 @pytest.mark.parametrize("persistent", [False, True])
 def test_intervals_equal_indices(lib, B, H, N, D, bq, bk, density, rep, persistent):

@@ -45,6 +45,14 @@ CASES = [
     (64, 64, 64, 2, 2, 333, 0.5, 0.3, 2.0),
     (128, 128, 128, 1, 1, 1, 1.0, 0.0, 1.0),       # a single token
     (128, 128, 128, 1, 1, 129, 1.0, 0.0, 1.0),     # tail block of one row / one key
+    # key blocks of 96, 160 and 192 keys (three or five sub-tiles per block; an odd total is padded)
+    (128, 128, 96, 1, 2, 1000, 0.5, 0.25, 2.0),
+    (128, 128, 160, 1, 2, 1111, 0.5, 0.2, 2.0),
+    (128, 128, 192, 1, 2, 1000, 0.5, 0.25, 2.0),
+    (128, 128, 192, 2, 1, 777, 0.35, 0.0, 1.0),
+    (128, 128, 96, 1, 1, 96 * 70 + 5, 1.0, 0.0, 1.0),   # 71 kept blocks in a row: the cached column list is refilled
+    (128, 128, 160, 1, 1, 97, 1.0, 0.0, 1.0),           # one short block
+    (128, 128, 192, 1, 1, 1, 1.0, 0.0, 1.0),
 ]
 
 
@@ -62,3 +70,45 @@ def test_random_masks(lib, D, bq, bk, B, H, N, dens, rep, gain):
         st = assert_parity(got, want, f"order {order}")
         assert_repeats_bitwise(got, repeat, bq, N)
     print(st, flush=True)
+
+
+@pytest.mark.parametrize("bk", [96, 160, 192])
+def test_wide_key_blocks_only_in_the_interleaved_kernel(lib, bk):
+    """The two-workgroup kernel is built for key blocks of 64 and 128 keys: asked for by name with
+    another width it refuses, it does not fall back."""
+    import torch
+
+    from paper_2603_05503_amd import binding
+    from tests.parity_utils import to_dev
+
+    print(f"bk={bk} forced two-workgroup kernel", flush=True)
+    N, H, D = 500, 1, 128
+    q, k, v = _qkv(5, 1, H, N, D)
+    mask = np.ones((H, -(-N // 128), -(-N // bk)), np.uint8)
+    dp = lib.compile_pattern(mask, None, H, N, 128, bk, 4).to_device()
+    tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
+    out = torch.empty_like(tq)
+    with pytest.raises(binding.CalibattError) as e:
+        binding.sparse_attn_fwd(tq, tk, tv, out, dp, 0.1, kernel=binding.KERNEL_TWO_WORKGROUPS)
+    assert e.value.status == -3
+
+
+def test_interleaved_kernel_by_name_is_the_default(lib):
+    import torch
+
+    from paper_2603_05503_amd import binding
+    from tests.parity_utils import from_dev, to_dev
+
+    print("kernel by name", flush=True)
+    N, H, D = 900, 2, 128
+    q, k, v = _qkv(6, 1, H, N, D, 2.0)
+    mask, repeat = random_mask(7, H, -(-N // 128), -(-N // 128), 0.5, 0.2, tail_partial=True)
+    dp = lib.compile_pattern(mask, repeat, H, N, 128, 128, 4).to_device()
+    tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
+    outs = []
+    for kern in (binding.KERNEL_AUTO, binding.KERNEL_INTERLEAVED):
+        out = torch.empty_like(tq)
+        binding.sparse_attn_fwd(tq, tk, tv, out, dp, 0.1, kernel=kern)
+        torch.cuda.synchronize()
+        outs.append(from_dev(out))
+    assert (outs[0] == outs[1]).all()
