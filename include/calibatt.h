@@ -195,7 +195,9 @@ int calibatt_compile_pattern(const uint8_t *mask, const int32_t *repeat, int H, 
  * scale    multiplies the logits before the softmax (1/sqrt(D) in Eq. 1).
  * stream   hipStream_t (NULL = default stream).  The call only enqueues work.
  *
- * Supported: D in {64, 128}, block_q and block_k in {64, 128}.
+ * Supported: D in {64, 128}, block_q and block_k in {64, 128}; with D = 128 and
+ * block_q = 128 also block_k in {96, 160, 192} (the key-block widths of the
+ * supplement's block-size ablation).
  * Errors: NULL, SHAPE, UNSUPPORTED, PATTERN_MISMATCH (pattern compiled for a
  * different H, N, block_q or block_k), LAUNCH.
  */
@@ -242,7 +244,8 @@ int calibatt_sparse_attn_fwd_strided(const void *q, const void *k, const void *v
  *           sub-tile as one instruction stream.
  *           CALIBATT_KERNEL_TWO_WORKGROUPS: the three phases of a tile run
  *           one after the other, two workgroups per CU overlap as they
- *           happen to fall; kept as the reference schedule.  Both meet the
+ *           happen to fall; kept as the reference schedule (key blocks of
+ *           64 and 128 keys only, UNSUPPORTED otherwise).  Both meet the
  *           same tolerance; their outputs differ in the last bits (the
  *           interleaved schedule moves the reference of its exponentials
  *           lazily).
