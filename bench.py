@@ -63,6 +63,9 @@ def parse_args():
     ap.add_argument("--no-energy", action="store_true", help="skip the calibration kernels (block energy, spatial similarity)")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the compact legs for the other named configurations and the sweep subset")
+    ap.add_argument("--dictionary", type=int, default=0, metavar="LAYERS",
+                    help="instead of the benchmark (no GPU needed): bytes of the kept-block lists of a synthetic "
+                         "50-step dictionary at the Wan-720p shape, LAYERS layers built and scaled to 40")
     ap.add_argument("--sweep-subset", type=int, default=200, help="patterns in the default run's sweep subset")
     ap.add_argument("--kernel", default="auto", choices=["auto", "2wg", "il"],
                     help="schedule of the forward (the `kernel` field of calibatt_fwd_options): the library's "
@@ -455,8 +458,92 @@ def sweep(args):
     }))
 
 
+def dictionary_report(layers, steps=50, heads=40, total_layers=40):
+    """Resident bytes of the kept-block lists of a whole calibrated dictionary (supplement A.2, A.3) at the
+    Wan-720p shape: one mask per (timestep, layer, head).  The masks come from the seeded generator
+    (workloads.dictionary_head_masks: later timesteps resemble each other, as the supplement observes of
+    calibrated masks); every count below is the output of a library call (calibatt_encode_intervals,
+    calibatt_merge_intervals, calibatt_share_timesteps).  ``layers`` layers are built, the totals scaled to
+    ``total_layers``.  Sharing is counted per (layer, head) cluster, the granularity of Section A.3."""
+    import numpy as np
+
+    import paper_2603_05503_amd as pkg
+    from paper_2603_05503_amd import binding
+    from workloads import dictionary_head_masks
+
+    pkg.load_library()
+
+    def csr(mask2d):
+        rows = mask2d != 0
+        row_ptr = np.zeros(rows.shape[0] + 1, np.int32)
+        np.cumsum(rows.sum(axis=1), out=row_ptr[1:])
+        return row_ptr, np.nonzero(rows)[1].astype(np.int32)
+
+    def interval_words(mask2d):
+        row_ptr, col_idx = csr(mask2d)
+        iv_ptr, iv = binding.encode_intervals(row_ptr, col_idx)
+        return int(iv.size), iv_ptr.size
+
+    totals = {k: 0 for k in ("masks", "kept_blocks", "index_bytes", "interval_bytes", "interval_bytes_merged95",
+                             "interval_bytes_shared_097", "interval_bytes_shared_098",
+                             "interval_bytes_merged95_shared_097", "kept_blocks_merged95",
+                             "kept_blocks_shared_097", "clusters_097", "clusters_098")}
+    runs_hist = []
+    t0 = time.perf_counter()
+    for layer in range(layers):
+        for head in range(heads):
+            masks = dictionary_head_masks(layer, head, steps)  # [steps, nb, nb]
+            nb = masks.shape[1]
+            per_row_ptr = (nb + 1) * 4
+            merged = np.empty_like(masks)
+            for t in range(steps):
+                words, _ = interval_words(masks[t])
+                kept = int(masks[t].sum())
+                totals["masks"] += 1
+                totals["kept_blocks"] += kept
+                totals["index_bytes"] += kept * 4 + per_row_ptr
+                totals["interval_bytes"] += words * 4 + per_row_ptr
+                runs_hist.append(words - nb)
+                merged[t], _ = binding.merge_intervals(masks[t], 95.0)
+                totals["interval_bytes_merged95"] += interval_words(merged[t])[0] * 4 + per_row_ptr
+                totals["kept_blocks_merged95"] += int(merged[t].sum())
+            for tau, tag in ((0.97, "097"), (0.98, "098")):
+                cluster, shared = binding.share_timesteps(masks, tau)
+                totals[f"clusters_{tag}"] += shared.shape[0]
+                totals[f"interval_bytes_shared_{tag}"] += sum(interval_words(m)[0] * 4 + per_row_ptr for m in shared)
+                if tag == "097":
+                    totals["kept_blocks_shared_097"] += int(shared[cluster].sum())
+            cluster, shared = binding.share_timesteps(merged, 0.97)
+            totals["interval_bytes_merged95_shared_097"] += sum(interval_words(m)[0] * 4 + per_row_ptr for m in shared)
+        print(f"dictionary: layer {layer + 1}/{layers} done, {time.perf_counter() - t0:.0f} s", file=sys.stderr, flush=True)
+    scale = total_layers / layers
+    gb = lambda key: round(totals[key] * scale / 1e9, 3)
+    dens = lambda key: round(totals[key] / (totals["masks"] * nb * nb), 4)
+    return {
+        "shape": f"Wan-720p: {steps} timesteps x {total_layers} layers x {heads} heads, {nb} x {nb} blocks per mask",
+        "built_layers": layers, "scaled_to_layers": total_layers,
+        "masks": "synthetic, seeded (workloads.dictionary_head_masks)",
+        "mean_runs_per_row": round(float(np.mean(runs_hist)) / nb, 2),
+        "density": dens("kept_blocks"),
+        "index_form_gb": gb("index_bytes"),
+        "interval_form_gb": gb("interval_bytes"),
+        "interval_form_merged_pct95_gb": gb("interval_bytes_merged95"),
+        "density_after_merging": dens("kept_blocks_merged95"),
+        "interval_form_shared_tau097_gb": gb("interval_bytes_shared_097"),
+        "interval_form_shared_tau098_gb": gb("interval_bytes_shared_098"),
+        "density_after_sharing_tau097": dens("kept_blocks_shared_097"),
+        "interval_form_merged_pct95_shared_tau097_gb": gb("interval_bytes_merged95_shared_097"),
+        "clusters_per_layer_head_tau097": round(totals["clusters_097"] / (layers * heads), 2),
+        "clusters_per_layer_head_tau098": round(totals["clusters_098"] / (layers * heads), 2),
+        "seconds": round(time.perf_counter() - t0, 1),
+    }
+
+
 def main():
     args = parse_args()
+    if args.dictionary > 0:
+        print(json.dumps({"dictionary": dictionary_report(args.dictionary)}))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (heads would shard across GPUs "
               "without any exchange)", file=sys.stderr)

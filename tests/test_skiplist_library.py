@@ -101,3 +101,20 @@ def test_sharing_hand_worked_and_errors():
     assert lib.calibatt_share_timesteps(None, *args[1:]) == -1
     assert lib.calibatt_share_timesteps(args[0], 0, *args[2:]) == -2
     assert lib.calibatt_share_timesteps(*args[:3], float("nan"), *args[4:]) == -2
+
+
+def test_dictionary_masks_share_at_late_timesteps():
+    """The time-coherent mask generator behind `bench.py --dictionary`: the kept fraction falls with the
+    timestep, late timesteps resemble each other, and the library clusters them exactly as the oracle does."""
+    from workloads import dictionary_head_masks
+
+    masks = dictionary_head_masks(0, 3, steps=12, name="wan480")
+    dens = masks.mean(axis=(1, 2))
+    assert masks.shape[0] == 12 and masks.shape[1] == masks.shape[2] and (np.diff(dens) <= 1e-9).all()
+    assert (masks[:, np.arange(masks.shape[1]), np.arange(masks.shape[1])] == 1).all()
+    cluster, shared = pkg.share_timesteps(masks, 0.9)
+    want_cluster, want_shared = sl.share_timesteps(masks.reshape(12, -1), 0.9)
+    assert cluster.tolist() == list(want_cluster)
+    assert (shared.reshape(len(want_shared), -1) == np.asarray(want_shared)).all()
+    assert shared.shape[0] < 12  # something is shared
+    assert sl.iou_skipped(masks[10].ravel(), masks[11].ravel()) > sl.iou_skipped(masks[0].ravel(), masks[1].ravel())

@@ -12,6 +12,7 @@ from .generators import (  # noqa: F401
     Workload,
     bf16_bits_to_f32,
     calibrated_like_mask,
+    dictionary_head_masks,
     f32_to_bf16_bits,
     make_qkv,
     make_workload,

@@ -395,3 +395,42 @@ def sweep_pattern(layer: int, step: int, heads: int = 40):
     geom: Geometry = cfg["geom"]
     mask, repeat, stats = calibrated_like_mask(seed + 100000, heads, geom.n_tokens, cfg["block"], geom, d, p)
     return mask, repeat, stats
+
+
+def dictionary_head_masks(layer: int, head: int, steps: int = 50, name: str = "wan720") -> np.ndarray:
+    """Masks of one (layer, head) over the timesteps of a generation, uint8 [steps, nb, nb]: a
+    synthetic stand-in for a calibrated dictionary whose masks resemble each other more and more
+    at later timesteps (supplement A.3).  One block score per head (spatial band and temporal
+    stripe as in ``calibrated_like_mask``), a kept fraction that falls with the timestep as the
+    many-step energy schedule does (exp(-16 t/T), supplement A.1), and a small score jitter per
+    step so that neighbouring steps differ in a few blocks.  Diagonal and one sink column forced."""
+    cfg = CONFIGS[name]
+    geom: Geometry = cfg["geom"]
+    N, block = geom.n_tokens, cfg["block"]
+    nb = -(-N // block)
+    rng = np.random.default_rng(BASE_SEED + 700000 + 1000 * layer + head)
+    centre = np.minimum(np.arange(nb, dtype=np.int64) * block + block // 2, geom.n_video - 1)
+    frame, off = centre // geom.per_frame, centre % geom.per_frame
+    dtok = np.abs(centre[:, None] - centre[None, :]).astype(np.float64)
+    doff = np.abs(off[:, None] - off[None, :]).astype(np.float64)
+    doff = np.minimum(doff, geom.per_frame - doff)
+    dfr = np.abs(frame[:, None] - frame[None, :]).astype(np.float64)
+    w_band = block * math.exp(rng.uniform(math.log(1.0), math.log(6.0)))
+    w_stripe = block * math.exp(rng.uniform(math.log(0.4), math.log(2.5)))
+    beta = rng.uniform(0.02, 0.4)
+    temp = np.exp(0.45 * _smooth_noise(rng, nb, max(2, nb // 24)))
+    band = np.where(frame[:, None] == frame[None, :], -dtok / w_band, -np.inf)
+    base = np.maximum(band, -(doff / w_stripe + beta * dfr)) / temp[:, None] + 0.15 * rng.standard_normal((nb, nb))
+    base[np.arange(nb), np.arange(nb)] = np.inf
+    base[:, 0] = np.inf
+    d_late = float(np.clip(cfg["density"] * rng.uniform(0.5, 1.5), 0.05, 0.9))
+    out = np.zeros((steps, nb, nb), dtype=np.uint8)
+    for t in range(steps):
+        d_t = d_late + (0.95 - d_late) * math.exp(-16.0 * t / steps)
+        score = base + 0.02 * rng.standard_normal((nb, nb))
+        k_keep = max(int(round(d_t * nb * nb)), 2 * nb)
+        flat = score.ravel()
+        keep = np.zeros(nb * nb, dtype=bool)
+        keep[np.argpartition(-flat, k_keep - 1)[:k_keep]] = True
+        out[t] = keep.reshape(nb, nb)
+    return out
