@@ -233,3 +233,36 @@ def test_mochi_shape_workspace_paths_agree_with_the_plain_ones():
     assert one.shape == (1, H, 350, 350)
     np.testing.assert_allclose(one, two, rtol=2e-3, atol=2e-7)
     np.testing.assert_allclose(one.sum(axis=-1), 1.0, rtol=0, atol=2e-4)
+
+
+@pytest.mark.parametrize("bk", [96, 192])
+def test_fullsize_wide_key_blocks(lib, bk):
+    """The Wan-480p tensors under a mask of 128 x 96 / 128 x 192 blocks (widths of the supplement's
+    block-size ablation), 30 % kept, 10 % repeated query blocks, interval form: sampled blocks against
+    the oracle, repeats bitwise, every element finite."""
+    import torch
+    from workloads import random_mask
+
+    print(f"full size wan480 with key blocks of {bk}", flush=True)
+    wl = _workload("wan480", None, "uniform", False)
+    nbq, nbk = wl.nbq, -(-wl.N // bk)
+    mask, repeat = random_mask(4242 + bk, wl.H, nbq, nbk, 0.3, 0.1, tail_partial=(wl.N % wl.block_q) != 0)
+    hp = lib.compile_pattern(mask, repeat, wl.H, wl.N, wl.block_q, bk, 4)
+    dp = hp.to_device(intervals=True)
+    q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
+    out = torch.empty_like(q)
+    out.view(torch.int16).fill_(0x7FC1)
+    lib.sparse_attn_fwd(q, k, v, out, dp, wl.scale)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all())
+    got = from_dev(out)
+    assert_repeats_bitwise(got, repeat, wl.block_q, wl.N)
+    rng = np.random.default_rng(bk)
+    items = sorted({(0, int(rng.integers(wl.H)), int(rng.integers(nbq))) for _ in range(24)} | {(0, 0, nbq - 1)})
+    want = sparse_attention_blocks(wl.q, wl.k, wl.v, mask, repeat, wl.scale, wl.block_q, bk, items)
+    worst = 0.0
+    for (b, h, r), w in zip(items, want):
+        g = bits_to_f64(got[b, h, r * wl.block_q : r * wl.block_q + w.shape[0]])
+        worst = max(worst, float(np.abs(g - w).max()))
+    print(f"bk={bk}: {len(items)} blocks, max_abs {worst:.3e}", flush=True)
+    assert worst <= MAX_ABS
