@@ -630,6 +630,7 @@ def main():
             "pattern_compile_ms": compile_ms,
             "pattern_form": "intervals" if args.intervals else "indices",
             "pattern_index_bytes": dp.index_bytes,
+            "kernel": {"auto": "interleaved (the library's choice)", "il": "interleaved", "2wg": "two workgroups (reference schedule)"}[args.kernel],
         },
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "kernel_ms_mean": ev_mean_ms,
