@@ -47,6 +47,9 @@ def _f64(bits, dtype):
     (2, 3, 1500, 128, 128, 128, True),
     (1, 2, 1000, 128, 64, 128, False),
     (1, 2, 777, 64, 128, 64, True),
+    (1, 2, 1100, 128, 128, 96, True),     # key blocks of three / five sub-tiles
+    (2, 2, 1100, 128, 128, 160, False),
+    (1, 2, 1100, 128, 128, 192, True),
 ])
 def test_dtype_and_lse_parity(lib, dtype, B, H, N, D, bq, bk, intervals):
     import torch

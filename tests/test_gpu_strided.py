@@ -21,7 +21,8 @@ def _qkv(seed, B, H, N, D, gain=2.0):
     return q, k, v
 
 
-@pytest.mark.parametrize("B,H,N,D,bq,bk", [(2, 3, 900, 128, 128, 128), (1, 4, 777, 64, 64, 64), (1, 2, 1000, 128, 64, 128)])
+@pytest.mark.parametrize("B,H,N,D,bq,bk", [(2, 3, 900, 128, 128, 128), (1, 4, 777, 64, 64, 64), (1, 2, 1000, 128, 64, 128),
+                                             (1, 3, 900, 128, 128, 160)])
 @pytest.mark.parametrize("intervals", [False, True])
 def test_strided_layouts_equal_packed(lib, B, H, N, D, bq, bk, intervals):
     import torch
