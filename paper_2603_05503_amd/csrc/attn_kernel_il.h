@@ -14,8 +14,10 @@
 // two wavefronts per SIMD keep the matrix pipe only about 60 % busy however
 // their phases happen to fall.  But an MFMA occupies the pipe for 32 cycles
 // and its wavefront can issue a few other instructions meanwhile.  So here a
-// kept 128-key block is cut into two 64-key sub-tiles, and in every STAGE a
-// wavefront issues, interleaved instruction by instruction,
+// kept key block is cut into sub-tiles of 64 keys (32 where the block is not
+// a multiple of 64 or is 64 keys itself), a row's kept blocks become one
+// stream of sub-tiles, and in every STAGE a wavefront issues, interleaved
+// instruction by instruction,
 //     the MFMAs of  O += P V  of the sub-tile before the previous one,
 //     the MFMAs of  S = K Q^T of the next sub-tile,
 //     the vector instructions of the softmax of the previous sub-tile
