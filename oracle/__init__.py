@@ -24,4 +24,4 @@ from .attention import (  # noqa: F401
 from .anchor import anchor_attention, anchor_rows, anchor_token_maps, nearest_anchor, spatial_similarity, spatial_similarity_rows  # noqa: F401
 from .calibration import block_energy, block_energy_rows, epsilon_schedule, flag_heads, schedule_base_level, schedule_constants, select_blocks, select_row, vote  # noqa: F401
 from . import skiplist  # noqa: F401
-from .pattern import compile_pattern, pair_rows, pattern_sizes, PatternError  # noqa: F401
+from .pattern import compile_pattern, pattern_sizes, PatternError  # noqa: F401

@@ -40,20 +40,6 @@ fan_ptr[n_work+1], fan_dst[n_repeat]
                     for work item i the ascending list of blocks r' of the same
                     head with repeat[h, r'] == r.
 
-pairs (pair_rows)   two neighbouring computed query blocks of a head worked on together,
-                    on the union of their kept columns, so that every key/value tile
-                    fetched serves both (Section 3.4 leaves the kernel's tiling free):
-                    per head the computed blocks in ascending r are paired off two by
-                    two (an odd one out stays alone).  Heads are visited as `work`
-                    lists them (group by group for orders 3 and 4, each group's heads
-                    in order of first appearance); a head's pairs are listed by the
-                    size of their union descending, then by their first block.
-                    pair_item[n_pairs][4]: position in `work` of the pair's first and
-                    second block (-1: none), size of the union, 0.
-                    pair_ptr[n_pairs+1], pair_cols[]: the union, ascending; bit 30 of
-                    an entry = the first block keeps the column, bit 31 = the second.
-                    pair_group_ptr[9]: segments of the pair list, as group_ptr.
-
 Rejected inputs (exceptions here, status codes in the library):
  range : repeat value outside {-1} U [0, nbq), or a block repeating itself
  chain : the source of a repeated block is itself repeated
@@ -173,47 +159,4 @@ def compile_pattern(mask, repeat, H, N, block_q, block_k, order=1):
         row_ptr=i32(row_ptr), col_idx=i32(col_idx), repeat_src=i32(rep),
         work=i32(work), fan_ptr=i32(fan_ptr), fan_dst=i32(fan_dst),
         n_groups=N_GROUPS if order in (3, 4) else 1, group_ptr=i32(group_ptr),
-    )
-
-
-def pair_rows(pattern):
-    """Pairs of neighbouring computed query blocks of a compiled pattern (dict returned by
-    compile_pattern) and the unions of their kept columns; see the module docstring."""
-    nbq = int(pattern["nbq"])
-    work = [int(x) for x in pattern["work"]]
-    row_ptr = pattern["row_ptr"]
-    col_idx = pattern["col_idx"]
-    pos = {rid: i for i, rid in enumerate(work)}
-    group_ptr = [int(x) for x in pattern["group_ptr"]]
-    n_groups = int(pattern["n_groups"])
-    items, ptr, cols, pair_group_ptr = [], [0], [], [0]
-    for g in range(n_groups):
-        segment = work[group_ptr[g]:group_ptr[g + 1]]
-        heads = []
-        for rid in segment:
-            if rid // nbq not in heads:
-                heads.append(rid // nbq)
-        for h in heads:
-            rows = sorted(rid for rid in segment if rid // nbq == h)
-            pairs = []
-            for i in range(0, len(rows), 2):
-                first = rows[i]
-                second = rows[i + 1] if i + 1 < len(rows) else None
-                kept_a = set(int(c) for c in col_idx[row_ptr[first]:row_ptr[first + 1]])
-                kept_b = set() if second is None else set(int(c) for c in col_idx[row_ptr[second]:row_ptr[second + 1]])
-                union = sorted(kept_a | kept_b)
-                pairs.append((first, second, [(c, c in kept_a, c in kept_b) for c in union]))
-            pairs.sort(key=lambda t: (-len(t[2]), t[0]))
-            for first, second, union in pairs:
-                items.append([pos[first], -1 if second is None else pos[second], len(union), 0])
-                cols.extend(c | (int(a) << 30) | (int(b) << 31) for c, a, b in union)
-                ptr.append(len(cols))
-        pair_group_ptr.append(len(items))
-    pair_group_ptr += [len(items)] * (N_GROUPS + 1 - len(pair_group_ptr))
-    return dict(
-        n_pairs=len(items),
-        pair_item=np.asarray(items, dtype=np.int32).reshape(-1, 4),
-        pair_ptr=np.asarray(ptr, dtype=np.int32),
-        pair_cols=np.asarray(cols, dtype=np.uint32),
-        pair_group_ptr=np.asarray(pair_group_ptr, dtype=np.int32),
     )

@@ -6,7 +6,7 @@ import os
 import numpy as np
 import pytest
 
-from oracle import PatternError, compile_pattern, pair_rows, pattern_sizes
+from oracle import PatternError, compile_pattern, pattern_sizes
 from workloads import random_mask
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -150,67 +150,6 @@ def check_invariants(p, mask, repeat, H, N, bq, bk, order):
             assert w.max() - w.min() <= max(per_head.values())
     else:
         assert p["n_groups"] == 1 and p["group_ptr"][0] == 0 and p["group_ptr"][1] == p["n_work"]
-
-
-def check_pairs_against_worked_example(pair_fn):
-    """pair_fn(mask, repeat, H, N, bq, bk, order) -> dict as returned by oracle.pair_rows."""
-    ex = load_worked_example()
-    mask = np.array(ex["mask"], dtype=np.uint8)
-    repeat = np.array(ex["repeat"], dtype=np.int32)
-    got = pair_fn(mask, repeat, ex["H"], ex["N"], ex["block_q"], ex["block_k"], 4)
-    want = ex["order4"]["pairs"]
-    assert got["n_pairs"] == len(want["pair_item"])
-    assert np.asarray(got["pair_item"]).tolist() == want["pair_item"]
-    assert np.asarray(got["pair_ptr"]).tolist() == want["pair_ptr"]
-    assert [int(x) for x in got["pair_cols"]] == [c | (a << 30) | (b << 31) for c, a, b in want["pair_cols"]]
-    assert np.asarray(got["pair_group_ptr"]).tolist() == want["pair_group_ptr"]
-
-
-def check_pair_invariants(pairs, p, nbq):
-    """What must hold of any pairing: every computed block in exactly one pair, partners are
-    neighbours among their head's computed blocks, the union is exactly the two lists merged."""
-    work = p["work"].astype(np.int64)
-    seen = []
-    for i in range(pairs["n_pairs"]):
-        a, b, n_union, zero = (int(x) for x in pairs["pair_item"][i])
-        assert zero == 0 and 0 <= a < work.size and -1 <= b < work.size
-        rows = [int(work[a])] + ([int(work[b])] if b >= 0 else [])
-        seen += rows
-        if b >= 0:
-            assert rows[0] // nbq == rows[1] // nbq and rows[0] < rows[1]
-            between = [r for r in work if rows[0] < r < rows[1]]
-            assert not between  # no computed block of the head lies between the partners
-        cols = pairs["pair_cols"][pairs["pair_ptr"][i]:pairs["pair_ptr"][i + 1]].astype(np.int64)
-        assert cols.size == n_union
-        col, in_a, in_b = cols & 0x3FFFFFFF, (cols >> 30) & 1, (cols >> 31) & 1
-        assert (np.diff(col) > 0).all() and ((in_a | in_b) == 1).all()
-        lists = [p["col_idx"][p["row_ptr"][r]:p["row_ptr"][r + 1]] for r in rows]
-        assert col[in_a == 1].tolist() == lists[0].tolist()
-        assert col[in_b == 1].tolist() == (lists[1].tolist() if b >= 0 else [])
-    assert sorted(seen) == sorted(work.tolist())
-    gp = np.asarray(pairs["pair_group_ptr"])
-    assert gp[0] == 0 and gp[-1] == pairs["n_pairs"] and (np.diff(gp) >= 0).all()
-
-
-def test_oracle_pairs_worked_example():
-    check_pairs_against_worked_example(lambda *a: pair_rows(compile_pattern(*a)))
-
-
-@pytest.mark.parametrize("seed", [0, 1, 2, 3])
-@pytest.mark.parametrize("order", [0, 1, 4])
-def test_oracle_pairs_invariants(seed, order):
-    H, nb = 5, 13
-    mask, repeat = random_mask(seed + 70, H, nb, nb, 0.35, 0.3)
-    mask[2, 4] = 0
-    p = compile_pattern(mask, repeat, H, nb * 16, 16, 16, order)
-    pairs = pair_rows(p)
-    check_pair_invariants(pairs, p, nb)
-    # the unions of a head are listed longest first
-    sizes = pairs["pair_item"][:, 2]
-    heads = p["work"][pairs["pair_item"][:, 0]] // nb
-    for i in range(1, pairs["n_pairs"]):
-        if heads[i] == heads[i - 1] and order == 4:
-            assert sizes[i] <= sizes[i - 1]
 
 
 def test_oracle_worked_example():
