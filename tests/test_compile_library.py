@@ -128,3 +128,24 @@ def test_library_error_codes_raw_abi():
     assert fwd(one, one, one, ctypes.c_void_p(32), 1, 1, 32, 64, 64, 64, ctypes.byref(cp), 1.0, None) == -8
     assert fwd(one, one, one, ctypes.c_void_p(32), 0, 1, 32, 64, 64, 64, ctypes.byref(cp), 1.0, None) == -2
     assert fwd(one, one, one, one, 1, 1, 32, 64, 64, 64, ctypes.byref(cp), 1.0, None) == -2  # out aliases q
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own, with warnings as errors."""
+    import shutil
+    import subprocess
+
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "calibatt.h"\n'
+                   "int main(void) {\n"
+                   "  calibatt_fwd_options options;\n"
+                   "  calibatt_pattern pattern;\n"
+                   "  (void)options;\n"
+                   "  (void)pattern;\n"
+                   "  return calibatt_version() > 0 ? 0 : 1;\n"
+                   "}\n")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
